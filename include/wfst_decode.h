@@ -1,0 +1,201 @@
+/*
+ * wfst_decode — batched, beam-pruned Viterbi token passing over a WFST decoding graph
+ * on one AMD MI355X (gfx950) GPU.
+ *
+ * The calls follow the decoder the paper describes (arXiv 1910.10032): a decoding graph
+ * held on the device in compressed-sparse-row form (Section 3.2.1, Eq. 1); many audio
+ * streams decoded at once, each owning a "channel" that keeps its state between calls,
+ * a call advancing a batch of channels ("lanes") by some frames of acoustic scores
+ * (Section 3.1); per frame, emitting arcs, then chains of non-emitting arcs, then
+ * pruning with an adaptive beam / max-active limit (Section 3, Fig. 1); and per-frame
+ * lattice preprocessing that keeps one representative token per FST state and records
+ * every other arc reaching it with its "extra cost" (Section 3.4).  Results come back as
+ * a best path and as raw lattice arcs.
+ *
+ * Conventions
+ *  - Every function that returns int returns 0 on success or a negative WFST_E_* code.
+ *    Nothing throws or aborts across this boundary.  Out-parameters are written only on
+ *    success, except the size reported with WFST_E_CAPACITY.
+ *  - HOST pointers are ordinary process memory; DEVICE pointers are GPU global memory on
+ *    the device that was current when the graph was loaded.  Each argument says which.
+ *  - The library owns all device memory it allocates.  The caller owns every buffer it
+ *    passes in and the acoustic-score tensors, which must stay valid until the work of
+ *    the advance call has completed on its stream.
+ *  - Costs are fp32 in the tropical semiring (smaller is better).  Each addition or
+ *    subtraction is rounded on its own (no fused multiply-add).
+ *  - Arc ids in results are positions in the caller's arc arrays.  WFST_NO_ARC marks
+ *    "no incoming arc" (the start token).
+ *  - Errors that concern one channel (token/lattice/history overflow, a channel with no
+ *    surviving token, NaN or +inf in the scores it read) are sticky for that channel,
+ *    stop that channel at the frame where they occur, and never disturb other channels.
+ *  - A graph may be shared by several decoders.  A decoder is not thread-safe.
+ */
+#ifndef WFST_DECODE_H
+#define WFST_DECODE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define WFST_NO_ARC 0xFFFFFFFFu
+
+enum {
+  WFST_OK = 0,
+  WFST_E_INVALID_ARG = -1,      /* null pointer, negative size, value out of range            */
+  WFST_E_BAD_GRAPH = -2,        /* malformed CSR (see wfst_decode_graph_load)                 */
+  WFST_E_BAD_CHANNEL = -3,      /* channel id out of range or repeated within one call        */
+  WFST_E_NOT_INIT = -4,         /* channel used before wfst_decode_init_channels              */
+  WFST_E_CAPACITY = -5,         /* caller's buffer too small; the needed size is reported     */
+  WFST_E_TOKEN_OVERFLOW = -6,   /* more candidate tokens in a frame than token_capacity       */
+  WFST_E_LATTICE_OVERFLOW = -7, /* lattice (or candidate) buffer of the channel is full       */
+  WFST_E_DEAD_CHANNEL = -8,     /* no token survived a frame                                  */
+  WFST_E_NAN_INPUT = -9,        /* a score read by the channel was NaN or +inf                */
+  WFST_E_BROKEN_TRACE = -10,    /* a best incoming arc starts at a state that holds no token  */
+  WFST_E_DEVICE = -11,          /* HIP runtime error (allocation, launch, copy)               */
+  WFST_E_HISTORY_OVERFLOW = -12 /* token history of the channel or max_frames exhausted       */
+};
+
+typedef struct wfst_graph wfst_graph_t;     /* opaque; device-resident, immutable            */
+typedef struct wfst_decoder wfst_decoder_t; /* opaque; owns all channel and lane state       */
+
+/* A decoding graph in CSR form.  All arrays are HOST memory, caller-owned, and copied
+ * during wfst_decode_graph_load.  Arcs of state s are [row_offsets[s], row_offsets[s+1]). */
+typedef struct {
+  int32_t num_states;
+  int64_t num_arcs;
+  int32_t start_state;
+  int32_t num_pdfs;           /* width of one row of acoustic scores                        */
+  const int64_t *row_offsets; /* [num_states + 1], non-decreasing, first 0, last num_arcs   */
+  const int32_t *ilabel;      /* [num_arcs] 0 = non-emitting (epsilon); else pdf id + 1     */
+  const int32_t *olabel;      /* [num_arcs] 0 = none; else word id                          */
+  const float *weight;        /* [num_arcs] fp32 cost, finite; >= 0 on non-emitting arcs    */
+  const int32_t *nextstate;   /* [num_arcs] destination state                               */
+  const float *final_cost;    /* [num_states] +INF = not final; otherwise finite            */
+} wfst_csr_t;
+
+/* Decoder hyper-parameters (Section 4: beam, lattice-beam, max-active; Section 3.2.1:
+ * number of channels and lanes) and the bounds of the decoder's buffers. */
+typedef struct {
+  float beam;                /* > 0                                                         */
+  float lattice_beam;        /* >= 0                                                        */
+  int32_t max_active;        /* >= 1: tokens kept per channel and frame                     */
+  int32_t num_channels;      /* streams whose state the decoder can hold                    */
+  int32_t max_lanes;         /* channels that one advance/init call can process             */
+  int32_t max_frames;        /* frames of scores one channel can consume between inits      */
+  int32_t token_capacity;    /* candidate tokens per lane and frame before pruning;
+                                0 = 4 * max_active                                          */
+  int32_t aux_capacity;      /* candidate arcs per lane and frame kept for lattice and
+                                back-pointer resolution; 0 = 2 * token_capacity             */
+  int64_t history_capacity;  /* tokens one channel can keep over all its frames;
+                                0 = (max_frames + 1) * max_active                           */
+  int64_t lattice_capacity;  /* lattice arcs one channel can buffer between readouts;
+                                0 = 64 * max_active                                         */
+  int32_t lattice_on;        /* 0: no lattice arcs are produced                             */
+} wfst_config_t;
+
+typedef struct { int32_t frame; uint32_t arc; float extra_cost; } wfst_lat_arc_t;
+typedef struct { int32_t state; float cost; uint32_t in_arc; } wfst_token_t;
+
+typedef struct {
+  int64_t frames;               /* token frames held, including frame 0 written by init     */
+  int64_t arcs_expanded;        /* sum over frames of the emitting out-degrees of the tokens
+                                   a frame starts from plus the non-emitting out-degrees of
+                                   the tokens within the beam after the closure             */
+  int64_t lattice_arcs;         /* lattice arcs produced so far (read out or not)           */
+  int32_t max_tokens_pre_prune; /* largest token count after the closure                    */
+  int32_t max_tokens;           /* largest token count kept                                 */
+  int32_t closure_iters_max;    /* most closure rounds in one frame (diagnostic only)       */
+  int32_t status;               /* sticky WFST_E_* of the channel, or 0                     */
+} wfst_stats_t;
+
+/* Validate and upload a graph.  WFST_E_BAD_GRAPH if offsets are not monotone, a
+ * destination or the start state is out of range, an ilabel is negative or exceeds
+ * num_pdfs, a weight is not finite, a non-emitting weight is negative, a final cost is
+ * NaN or -inf, or num_states + num_arcs >= 2^31 - 1.  On the device the graph takes
+ * 12*(num_states + num_arcs) bytes for decoding (the paper's Eq. 1 plus 4 bytes per
+ * non-emitting arc) and 8*(num_states + num_arcs) bytes used only by readouts. */
+int wfst_decode_graph_load(const wfst_csr_t *csr, wfst_graph_t **out);
+void wfst_decode_graph_free(wfst_graph_t *graph);
+/* Device bytes of the graph: the part read while decoding, and the readout-only part. */
+int wfst_decode_graph_bytes(const wfst_graph_t *graph, int64_t *decode_bytes, int64_t *readout_bytes);
+
+/* Create a decoder and allocate all its device memory (nothing is allocated later
+ * except temporary readout staging).  The graph must outlive the decoder. */
+int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, wfst_decoder_t **out);
+void wfst_decode_destroy(wfst_decoder_t *decoder);
+/* Device bytes held per parked channel, per lane, and in total. */
+int wfst_decode_state_bytes(const wfst_decoder_t *decoder, int64_t *per_channel, int64_t *per_lane, int64_t *total);
+
+/* Start (or restart) streams: each listed channel gets the start token and its closure
+ * as frame 0.  channels: HOST [n], distinct, each in [0, num_channels); n may exceed
+ * max_lanes (processed in groups).  Synchronises with the device before returning. */
+int wfst_decode_init_channels(wfst_decoder_t *decoder, const int32_t *channels, int32_t n);
+/* Mark channels unused; their buffers are reused by the next init. */
+int wfst_decode_free_channels(wfst_decoder_t *decoder, const int32_t *channels, int32_t n);
+
+/* Advance n_lanes channels: lane i consumes n_frames[i] rows of scores.
+ *   channels  HOST [n_lanes]  distinct initialised channel ids, n_lanes <= max_lanes
+ *   loglikes  HOST [n_lanes]  array of DEVICE pointers; lane i's rows are fp32
+ *                             [n_frames[i]][strides[i]], already acoustically scaled;
+ *                             the decoder reads column pdf of the current row
+ *   strides   HOST [n_lanes]  row pitch in floats, >= num_pdfs
+ *   n_frames  HOST [n_lanes]  >= 0; lanes may differ (a lane with fewer frames stops early)
+ *   stream    hipStream_t on which the work is enqueued, or NULL for the default stream
+ * Returns once the work is enqueued.  Per-channel failures are recorded in the channel's
+ * sticky status, visible through the readout calls and wfst_decode_stats. */
+int wfst_decode_advance(wfst_decoder_t *decoder, const int32_t *channels, int32_t n_lanes,
+                        const float *const *loglikes, const int32_t *strides,
+                        const int32_t *n_frames, void *stream);
+
+/* Best path of each listed channel over all frames decoded so far.
+ *   use_final      1: minimise token cost + final cost over final states (falling back
+ *                  to 0 when no final state holds a token); 0: minimise token cost
+ *   words          HOST [n * words_cap]  channel i's non-zero olabels, in path order, at
+ *                  words + i * words_cap
+ *   n_words, total_cost, reached_final, status   HOST [n]
+ * status[i] receives the channel's own result code (0, its sticky error,
+ * WFST_E_BROKEN_TRACE, or WFST_E_CAPACITY with n_words[i] = needed size).  The function
+ * itself fails only for invalid arguments or device errors.  Synchronises. */
+int wfst_decode_best_path_batch(wfst_decoder_t *decoder, const int32_t *channels, int32_t n,
+                                int32_t use_final, int32_t *words, int32_t words_cap,
+                                int32_t *n_words, float *total_cost, int32_t *reached_final,
+                                int32_t *status);
+/* Single-channel form; returns the channel's result code. */
+int wfst_decode_best_path(wfst_decoder_t *decoder, int32_t channel, int32_t use_final,
+                          int32_t *words, int32_t cap, int32_t *n_words, float *total_cost,
+                          int32_t *reached_final);
+/* Arcs (caller's ids, path order) of the best path of one channel.  arcs: HOST [cap]. */
+int wfst_decode_best_path_arcs(wfst_decoder_t *decoder, int32_t channel, int32_t use_final,
+                               uint32_t *arcs, int32_t cap, int32_t *n_arcs, float *total_cost,
+                               int32_t *reached_final);
+
+/* Drain the lattice arcs buffered for a channel since its last readout.  Records with
+ * frame < from_frame are discarded, the others are copied to `out` in no particular
+ * order (HOST memory if out_is_device == 0, else DEVICE memory), and the buffer is
+ * emptied.  If cap is too small: WFST_E_CAPACITY, *n = needed, nothing is drained.
+ * Synchronises. */
+int wfst_decode_lattice_arcs(wfst_decoder_t *decoder, int32_t channel, int32_t from_frame,
+                             wfst_lat_arc_t *out, int64_t cap, int64_t *n, int32_t out_is_device);
+
+/* Tokens kept for one frame of a channel (frame -1 = last), in no particular order.
+ * out: HOST [cap].  A parity hook: the token history is what best_path walks. */
+int wfst_decode_tokens(wfst_decoder_t *decoder, int32_t channel, int32_t frame,
+                       wfst_token_t *out, int32_t cap, int32_t *n);
+
+int wfst_decode_stats(wfst_decoder_t *decoder, int32_t channel, wfst_stats_t *out);
+
+/* Per-kernel timing with HIP events on the stream of each call (off by default).  While
+ * on, every advance call is bracketed by an event pair; wfst_decode_profile waits for
+ * the recorded work and returns the number of advance launches and their summed
+ * duration since profiling was switched on or last read. */
+int wfst_decode_set_profiling(wfst_decoder_t *decoder, int32_t on);
+int wfst_decode_profile(wfst_decoder_t *decoder, int64_t *launches, double *total_ms);
+
+const char *wfst_decode_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WFST_DECODE_H */
