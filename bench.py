@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the decoding hot path on one MI355X.
+
+Workload: benchmark configs[3] — the 8M-state / 23M-arc synthetic decoding graph,
+500 concurrent channels fed 50-frame chunks, beam 13, max-active 7000, lattice beam 6,
+with a best-path and a lattice-arc readout for every channel after every chunk.
+
+A "step" is one pass of the whole hot path over one batch: all 500 lanes advance by one
+50-frame chunk (emitting expansion, closure, pruning, lattice records), followed by the
+per-chunk readouts.  Scores are generated on the device beforehand and are resident in
+HBM when the timed region starts.  value = seconds of audio decoded per wall second at
+10 ms per frame (RTFx), whole job.
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+FRAME_SHIFT_S = 0.010
+HBM_PEAK_GBS = 8000.0
+# Algorithmic HBM bytes per expanded arc (derivation in DESIGN.md, "Algorithmic bytes"):
+# 12 B arc record + (12 B state header + 16 B token read) / 2.875 arcs per token
+# + 1 B of score row per arc + 16 B token written and 12 B lattice record per kept token
+# (about 0.35 kept tokens per arc) ~= 33 B.
+ALGO_BYTES_PER_ARC = 33.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=36)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--channels", type=int, default=0, help="override the number of channels (default: the config's 500)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-readout", action="store_true", help="time the advance calls only")
+    ap.add_argument("--cpu-streams", type=int, default=12)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build decodes on one GPU only (streams are independent; more GPUs would each "
+              "run their own decoder on a share of the channels) — run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import synth
+    from paper_1910_10032_amd import binding as B
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    cfg = synth.configs()[3]
+    n_ch = args.channels or cfg.n_streams
+    chunk = cfg.chunk
+    K, W = args.steps, args.warmup
+    n_frames = (K + W) * chunk
+    assert n_frames <= cfg.len_hi, f"steps + warmup must be <= {cfg.len_hi // chunk} chunks of {chunk} frames"
+    P = cfg.graph.num_pdfs
+
+    t_setup = time.perf_counter()
+    g = synth.make_graph(cfg.graph)
+    graph = B.WfstGraph(g)
+    dec = B.WfstDecoder(graph, cfg.beam, cfg.lattice_beam, cfg.max_active, num_channels=n_ch, max_lanes=n_ch,
+                        max_frames=n_frames, token_capacity=16384, history_capacity=2_500_000,
+                        lattice_capacity=400_000)
+    scores = torch.empty((n_ch, n_frames, P), dtype=torch.float32, device="cuda")
+    for s in range(n_ch):
+        synth.device_loglikes(scores[s], cfg.ll_seed, s, 0, cfg.ll_mu, cfg.ll_sigma, cfg.ll_boost)
+    torch.cuda.synchronize()
+    chans = list(range(n_ch))
+    dec.init_channels(chans)
+    lat_buf = torch.empty(n_ch * 80_000 * 12, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+
+    ch_np = np.arange(n_ch, dtype=np.int32)
+    strides_np = np.full(n_ch, P, np.int32)
+    nfr_np = np.full(n_ch, chunk, np.int32)
+    row0 = scores.data_ptr() + np.arange(n_ch, dtype=np.uint64) * np.uint64(n_frames * P * 4)
+
+    def step(i: int, readout: bool):
+        ptrs = row0 + np.uint64(i * chunk * P * 4)
+        dec.advance_ptrs(ch_np, ptrs, strides_np, nfr_np, stream)
+        if readout:
+            paths = dec.best_path_batch(chans, use_final=False, words_cap=1024)
+            offs = dec.lattice_arcs_batch(chans, out_device=lat_buf)
+            return paths, offs
+        return None
+
+    readout = not args.no_readout
+    for i in range(W):
+        step(i, readout)
+    torch.cuda.synchronize()
+    arcs0 = sum(dec.stats(c)["arcs_expanded"] for c in chans)
+    dec.set_profiling(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    last = None
+    for i in range(W, W + K):
+        last = step(i, readout)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    launches, kernel_ms = dec.profile()
+    dec.set_profiling(False)
+    stats = [dec.stats(c) for c in chans]
+    bad = [(c, s["status"]) for c, s in zip(chans, stats) if s["status"] != 0]
+    assert not bad, f"channels stopped with an error: {bad[:5]}"
+    arcs = sum(s["arcs_expanded"] for s in stats) - arcs0
+    wall = t1 - t0
+    audio_s = K * n_ch * chunk * FRAME_SHIFT_S
+    rtfx = audio_s / wall
+    avg_launch_s = kernel_ms / 1e3 / max(launches, 1)
+    arcs_per_launch = arcs / max(launches, 1)
+    achieved = ALGO_BYTES_PER_ARC * arcs_per_launch / avg_launch_s / 1e9
+
+    result = {
+        "metric": "decode RTFx (audio s / wall s) + arcs expanded/s, batched streams, 1 GPU",
+        "value": round(rtfx, 1), "unit": "x real time (10 ms frames)", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(wall / K * 1e3, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "configs[3]: 8M-state/23M-arc synthetic graph, %d channels x %d-frame chunks, beam %g, "
+                               "max-active %d, lattice-beam %g, per-chunk best-path + lattice readout%s"
+                               % (n_ch, chunk, cfg.beam, cfg.max_active, cfg.lattice_beam, "" if readout else " (readout off)"),
+                   "channels": n_ch, "chunk_frames": chunk, "stream_frames_timed": K * n_ch * chunk},
+        "arcs_expanded_per_s": round(arcs / wall, 1),
+        "stream_frames_per_s": round(K * n_ch * chunk / wall, 1),
+        "arcs_per_stream_frame": round(arcs / (K * n_ch * chunk), 1),
+        "advance_kernel_ms_per_step": round(kernel_ms / max(launches, 1), 3),
+        "max_tokens_pre_prune": max(s["max_tokens_pre_prune"] for s in stats),
+        "max_tokens": max(s["max_tokens"] for s in stats),
+        "roofline": {"bound": "hbm", "kernel": "k_advance", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                     "algorithmic_bytes_per_arc": ALGO_BYTES_PER_ARC, "launches": launches,
+                     "avg_launch_ms": round(avg_launch_s * 1e3, 4)},
+        "setup_s": round(t0 - t_setup, 1),
+    }
+    if last is not None:
+        result["lattice_arcs_last_chunk"] = int(last[1][-1])
+
+    if not args.no_cpu_baseline:
+        import oracle
+        og = oracle.OracleGraph(g)
+        ns = args.cpu_streams
+        t_c = time.perf_counter()
+        c_arcs, c_frames = 0, 0
+        for s in range(ns):
+            od = oracle.OracleDecoder(og, cfg.beam, cfg.lattice_beam, cfg.max_active)
+            rows = cfg.loglikes(s, 0, n_frames)
+            od.advance(rows)
+            c_arcs += od.arcs_expanded
+            c_frames += n_frames
+        # time of the decoding alone: regenerate the rows outside the clock
+        t_gen = time.perf_counter()
+        for s in range(ns):
+            cfg.loglikes(s, 0, n_frames)
+        t_end = time.perf_counter()
+        cpu_wall = (t_gen - t_c) - (t_end - t_gen)
+        result["cpu_baseline"] = {"value": round(c_frames * FRAME_SHIFT_S / cpu_wall, 2), "unit": "x real time (10 ms frames)",
+                                  "cores": 1, "kind": "oracle",
+                                  "sample": f"streams 0..{ns - 1} of the same workload, {n_frames} frames each, one thread",
+                                  "arcs_expanded_per_s": round(c_arcs / cpu_wall, 1)}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

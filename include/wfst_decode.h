@@ -175,9 +175,18 @@ int wfst_decode_best_path_arcs(wfst_decoder_t *decoder, int32_t channel, int32_t
  * frame < from_frame are discarded, the others are copied to `out` in no particular
  * order (HOST memory if out_is_device == 0, else DEVICE memory), and the buffer is
  * emptied.  If cap is too small: WFST_E_CAPACITY, *n = needed, nothing is drained.
- * Synchronises. */
+ * A channel that died or met a bad score still hands out the arcs of its earlier frames;
+ * a channel stopped by an overflow returns that error.  Synchronises. */
 int wfst_decode_lattice_arcs(wfst_decoder_t *decoder, int32_t channel, int32_t from_frame,
                              wfst_lat_arc_t *out, int64_t cap, int64_t *n, int32_t out_is_device);
+
+/* Drain several channels at once into one buffer: channel i's arcs land at
+ * out[offsets[i] .. offsets[i+1]) (offsets: HOST [n + 1]).  A channel stopped by an
+ * overflow contributes nothing.  If cap < offsets[n]: WFST_E_CAPACITY, offsets are still
+ * filled in, nothing is drained.  Synchronises. */
+int wfst_decode_lattice_arcs_batch(wfst_decoder_t *decoder, const int32_t *channels, int32_t n,
+                                   wfst_lat_arc_t *out, int64_t cap, int64_t *offsets,
+                                   int32_t out_is_device);
 
 /* Tokens kept for one frame of a channel (frame -1 = last), in no particular order.
  * out: HOST [cap].  A parity hook: the token history is what best_path walks. */

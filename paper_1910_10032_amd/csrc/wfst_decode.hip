@@ -1,0 +1,549 @@
+// Host side of the wfst_decode C ABI (declared in include/wfst_decode.h): graph validation
+// and device layout, decoder memory, launches and readouts.  Every step of the decoding
+// path itself runs in the kernels of wfst_kernels.h.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/wfst_decode.h"
+#include "wfst_kernels.h"
+
+using namespace wfst;
+
+#define HIP_TRY(expr) do { if ((expr) != hipSuccess) { (void)hipGetLastError(); return WFST_E_DEVICE; } } while (0)
+
+static_assert(sizeof(LatRec) == sizeof(wfst_lat_arc_t), "lattice record layout");
+static_assert(sizeof(TokOut) == sizeof(wfst_token_t), "token layout");
+static_assert(sizeof(Slot) == 16 && sizeof(HTok) == 16 && sizeof(Aux) == 16, "16-byte records");
+
+constexpr int NT = 512;          // threads of the workgroup that owns a lane
+constexpr int PARAM_RING = 8;    // pinned staging buffers for lane parameters
+
+struct wfst_graph {
+  GraphDev dev{};
+  int device = 0;
+  int32_t num_states = 0;
+  int64_t num_arcs = 0;
+  int64_t decode_bytes = 0, readout_bytes = 0;
+};
+
+struct wfst_decoder {
+  const wfst_graph *graph = nullptr;
+  wfst_config_t cfg{};
+  DecDev dev{};
+  int64_t per_channel_bytes = 0, per_lane_bytes = 0, total_bytes = 0;
+  std::vector<void *> allocs;
+  std::vector<uint8_t> inited;          // host mirror: channel has been initialised
+  std::vector<int64_t> frames_fed;      // host mirror: rows of scores handed to the channel
+  std::vector<uint32_t> stamp;          // duplicate detection within a call
+  uint32_t stamp_now = 0;
+  LaneParam *d_params = nullptr;        // [max_lanes]
+  LaneParam *h_params[PARAM_RING] = {};
+  hipEvent_t param_ev[PARAM_RING] = {};
+  int ring_pos = 0;
+  int32_t *d_chans = nullptr;           // readout scratch [max(num_channels, max_lanes)]
+  PathOut *d_pathout = nullptr;
+  void *d_stage = nullptr; size_t stage_bytes = 0;
+  unsigned long long *d_cnt = nullptr;
+  long long *d_offs = nullptr;          // readout scratch [max(num_channels, max_lanes) + 1]
+  bool profiling = false;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
+};
+
+namespace {
+
+template <class T> int dev_alloc(wfst_decoder *d, T **p, size_t n) {
+  void *q = nullptr;
+  size_t bytes = std::max<size_t>(n, 1) * sizeof(T);
+  if (hipMalloc(&q, bytes) != hipSuccess) { (void)hipGetLastError(); return WFST_E_DEVICE; }
+  d->allocs.push_back(q);
+  d->total_bytes += (int64_t)bytes;
+  *p = (T *)q;
+  return 0;
+}
+
+int ensure_stage(wfst_decoder *d, size_t bytes) {
+  if (bytes <= d->stage_bytes) return 0;
+  if (d->d_stage) HIP_TRY(hipFree(d->d_stage));
+  d->d_stage = nullptr; d->stage_bytes = 0;
+  size_t want = std::max<size_t>(bytes, 1 << 20);
+  HIP_TRY(hipMalloc(&d->d_stage, want));
+  d->stage_bytes = want;
+  return 0;
+}
+
+int check_channels(wfst_decoder *d, const int32_t *channels, int32_t n, bool need_init) {
+  if (!channels && n > 0) return WFST_E_INVALID_ARG;
+  if (++d->stamp_now == 0) { std::fill(d->stamp.begin(), d->stamp.end(), 0u); d->stamp_now = 1; }
+  for (int32_t i = 0; i < n; ++i) {
+    const int32_t c = channels[i];
+    if (c < 0 || c >= d->cfg.num_channels) return WFST_E_BAD_CHANNEL;
+    if (d->stamp[c] == d->stamp_now) return WFST_E_BAD_CHANNEL;
+    d->stamp[c] = d->stamp_now;
+    if (need_init && !d->inited[c]) return WFST_E_NOT_INIT;
+  }
+  return 0;
+}
+
+// Stage lane parameters through a pinned ring and launch the lane kernel.
+int launch_lanes(wfst_decoder *d, const std::vector<LaneParam> &lp, int is_init, hipStream_t stream) {
+  const int n = (int)lp.size();
+  if (n == 0) return 0;
+  const int slot = d->ring_pos;
+  d->ring_pos = (d->ring_pos + 1) % PARAM_RING;
+  HIP_TRY(hipEventSynchronize(d->param_ev[slot]));           // its previous copy has been consumed
+  std::memcpy(d->h_params[slot], lp.data(), sizeof(LaneParam) * (size_t)n);
+  HIP_TRY(hipMemcpyAsync(d->d_params, d->h_params[slot], sizeof(LaneParam) * (size_t)n, hipMemcpyHostToDevice, stream));
+  HIP_TRY(hipEventRecord(d->param_ev[slot], stream));
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (d->profiling && !is_init) {
+    HIP_TRY(hipEventCreate(&e0)); HIP_TRY(hipEventCreate(&e1));
+    HIP_TRY(hipEventRecord(e0, stream));
+  }
+  hipLaunchKernelGGL(k_advance<NT>, dim3(n), dim3(NT), 0, stream, d->dev, (const LaneParam *)d->d_params, is_init);
+  HIP_TRY(hipGetLastError());
+  if (e0) { HIP_TRY(hipEventRecord(e1, stream)); d->prof_events.push_back({e0, e1}); }
+  return 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *wfst_decode_strerror(int code) {
+  switch (code) {
+    case WFST_OK: return "ok";
+    case WFST_E_INVALID_ARG: return "invalid argument";
+    case WFST_E_BAD_GRAPH: return "malformed graph";
+    case WFST_E_BAD_CHANNEL: return "channel id out of range or repeated";
+    case WFST_E_NOT_INIT: return "channel not initialised";
+    case WFST_E_CAPACITY: return "caller buffer too small";
+    case WFST_E_TOKEN_OVERFLOW: return "token capacity exceeded";
+    case WFST_E_LATTICE_OVERFLOW: return "lattice capacity exceeded";
+    case WFST_E_DEAD_CHANNEL: return "no token survived";
+    case WFST_E_NAN_INPUT: return "NaN or +inf acoustic score";
+    case WFST_E_BROKEN_TRACE: return "back-pointer chain is broken";
+    case WFST_E_DEVICE: return "HIP runtime error";
+    case WFST_E_HISTORY_OVERFLOW: return "token history or max_frames exceeded";
+    default: return "unknown error";
+  }
+}
+
+int wfst_decode_graph_load(const wfst_csr_t *csr, wfst_graph_t **out) {
+  if (!csr || !out) return WFST_E_INVALID_ARG;
+  const int32_t Q = csr->num_states;
+  const int64_t E = csr->num_arcs;
+  if (Q < 1 || E < 0 || csr->num_pdfs < 1) return WFST_E_INVALID_ARG;
+  if (!csr->row_offsets || !csr->final_cost) return WFST_E_INVALID_ARG;
+  if (E > 0 && (!csr->ilabel || !csr->olabel || !csr->weight || !csr->nextstate)) return WFST_E_INVALID_ARG;
+  if ((int64_t)Q + E >= 0x7FFFFFFFll - 1) return WFST_E_BAD_GRAPH;
+  if (csr->start_state < 0 || csr->start_state >= Q) return WFST_E_BAD_GRAPH;
+  if (csr->row_offsets[0] != 0 || csr->row_offsets[Q] != E) return WFST_E_BAD_GRAPH;
+  for (int32_t s = 0; s < Q; ++s) {
+    if (csr->row_offsets[s + 1] < csr->row_offsets[s] || csr->row_offsets[s + 1] > E) return WFST_E_BAD_GRAPH;
+    const float f = csr->final_cost[s];
+    if (f != f || f == -INFINITY) return WFST_E_BAD_GRAPH;
+  }
+  for (int64_t a = 0; a < E; ++a) {
+    if (csr->nextstate[a] < 0 || csr->nextstate[a] >= Q) return WFST_E_BAD_GRAPH;
+    if (csr->ilabel[a] < 0 || csr->ilabel[a] > csr->num_pdfs) return WFST_E_BAD_GRAPH;
+    if (!std::isfinite(csr->weight[a])) return WFST_E_BAD_GRAPH;
+    if (csr->ilabel[a] == 0 && csr->weight[a] < 0.f) return WFST_E_BAD_GRAPH;
+  }
+  // record layout: header of state s at handle[s] = s + (arcs of earlier states)
+  const size_t R = (size_t)Q + (size_t)E;
+  std::vector<uint32_t> rec, orig; std::vector<int32_t> label; std::vector<uint8_t> has_eps;
+  try {
+    rec.resize(3 * R); orig.assign(R, NO_ARC); label.resize(R); has_eps.assign(Q, 0);
+  } catch (const std::bad_alloc &) { return WFST_E_DEVICE; }
+  auto handle_of = [&](int32_t s) { return (uint32_t)((int64_t)s + csr->row_offsets[s]); };
+  for (int32_t s = 0; s < Q; ++s)
+    for (int64_t a = csr->row_offsets[s]; a < csr->row_offsets[s + 1]; ++a)
+      if (csr->ilabel[a] == 0) { has_eps[s] = 1; break; }
+  auto f2u = [](float x) { uint32_t u; std::memcpy(&u, &x, 4); return u; };
+  for (int32_t s = 0; s < Q; ++s) {
+    const uint32_t h = handle_of(s);
+    uint32_t ne = 0, np = 0;
+    for (int64_t a = csr->row_offsets[s]; a < csr->row_offsets[s + 1]; ++a) (csr->ilabel[a] ? ne : np)++;
+    rec[3 * (size_t)h] = ne; rec[3 * (size_t)h + 1] = np; rec[3 * (size_t)h + 2] = f2u(csr->final_cost[s]);
+    label[h] = s;
+    uint32_t re = h + 1, rp = h + 1 + ne;            // next emitting / epsilon record
+    for (int64_t a = csr->row_offsets[s]; a < csr->row_offsets[s + 1]; ++a) {
+      const int32_t d = csr->nextstate[a];
+      const uint32_t r = csr->ilabel[a] ? re++ : rp++;
+      rec[3 * (size_t)r] = handle_of(d) | (has_eps[d] ? HAS_EPS : 0u);
+      rec[3 * (size_t)r + 1] = f2u(csr->weight[a]);
+      rec[3 * (size_t)r + 2] = csr->ilabel[a] ? (uint32_t)(csr->ilabel[a] - 1) : (uint32_t)csr->olabel[a];
+      label[r] = csr->olabel[a];
+      orig[r] = (uint32_t)a;
+    }
+  }
+  wfst_graph *g = new (std::nothrow) wfst_graph;
+  if (!g) return WFST_E_DEVICE;
+  (void)hipGetDevice(&g->device);
+  uint32_t *d_rec = nullptr, *d_orig = nullptr; int32_t *d_label = nullptr;
+  bool ok = hipMalloc((void **)&d_rec, sizeof(uint32_t) * 3 * R) == hipSuccess &&
+            hipMalloc((void **)&d_orig, sizeof(uint32_t) * R) == hipSuccess &&
+            hipMalloc((void **)&d_label, sizeof(int32_t) * R) == hipSuccess &&
+            hipMemcpy(d_rec, rec.data(), sizeof(uint32_t) * 3 * R, hipMemcpyHostToDevice) == hipSuccess &&
+            hipMemcpy(d_orig, orig.data(), sizeof(uint32_t) * R, hipMemcpyHostToDevice) == hipSuccess &&
+            hipMemcpy(d_label, label.data(), sizeof(int32_t) * R, hipMemcpyHostToDevice) == hipSuccess;
+  if (!ok) {
+    (void)hipGetLastError();
+    if (d_rec) (void)hipFree(d_rec);
+    if (d_orig) (void)hipFree(d_orig);
+    if (d_label) (void)hipFree(d_label);
+    delete g;
+    return WFST_E_DEVICE;
+  }
+  g->dev.rec = d_rec; g->dev.orig = d_orig; g->dev.label = d_label;
+  g->dev.num_records = (uint32_t)R; g->dev.start_handle = handle_of(csr->start_state); g->dev.num_pdfs = csr->num_pdfs;
+  g->num_states = Q; g->num_arcs = E;
+  g->decode_bytes = (int64_t)(12 * R); g->readout_bytes = (int64_t)(8 * R);
+  *out = g;
+  return 0;
+}
+
+void wfst_decode_graph_free(wfst_graph_t *g) {
+  if (!g) return;
+  (void)hipFree((void *)g->dev.rec); (void)hipFree((void *)g->dev.orig); (void)hipFree((void *)g->dev.label);
+  delete g;
+}
+
+int wfst_decode_graph_bytes(const wfst_graph_t *g, int64_t *decode_bytes, int64_t *readout_bytes) {
+  if (!g) return WFST_E_INVALID_ARG;
+  if (decode_bytes) *decode_bytes = g->decode_bytes;
+  if (readout_bytes) *readout_bytes = g->readout_bytes;
+  return 0;
+}
+
+int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, wfst_decoder_t **out) {
+  if (!graph || !config || !out) return WFST_E_INVALID_ARG;
+  wfst_config_t c = *config;
+  if (!(c.beam > 0.f) || !(c.lattice_beam >= 0.f) || c.max_active < 1 || c.num_channels < 1 || c.max_lanes < 1 ||
+      c.max_frames < 1 || c.token_capacity < 0 || c.aux_capacity < 0 || c.history_capacity < 0 || c.lattice_capacity < 0)
+    return WFST_E_INVALID_ARG;
+  if (c.max_active > (1 << 26)) return WFST_E_INVALID_ARG;
+  if (c.token_capacity == 0) c.token_capacity = (int32_t)std::min<int64_t>(4ll * c.max_active, 1 << 28);
+  if (c.token_capacity < 2 || c.token_capacity > (1 << 28)) return WFST_E_INVALID_ARG;
+  if (c.aux_capacity == 0) c.aux_capacity = (int32_t)std::min<int64_t>(2ll * c.token_capacity, 1 << 29);
+  if (c.history_capacity == 0) c.history_capacity = ((int64_t)c.max_frames + 1) * c.max_active;
+  if (c.lattice_capacity == 0) c.lattice_capacity = 64ll * c.max_active;
+  wfst_decoder *d = new (std::nothrow) wfst_decoder;
+  if (!d) return WFST_E_DEVICE;
+  d->graph = graph; d->cfg = c;
+  DecDev &D = d->dev;
+  D.g = graph->dev;
+  int hbits = 4;
+  while ((1ll << hbits) < 2ll * c.token_capacity) ++hbits;
+  D.H = 1u << hbits; D.hbits = hbits;
+  D.qcap = (int32_t)std::min<int64_t>(2ll * c.token_capacity, 0x3FFFFFFF);
+  D.auxcap = c.aux_capacity; D.tokcap = c.token_capacity; D.max_frames = c.max_frames; D.max_active = c.max_active;
+  D.lattice_on = c.lattice_on ? 1 : 0; D.beam = c.beam; D.lattice_beam = c.lattice_beam;
+  D.hist_cap = c.history_capacity; D.lat_cap = c.lattice_on ? c.lattice_capacity : 1;
+  const size_t nc = (size_t)c.num_channels, nl = (size_t)c.max_lanes;
+  int rc = 0;
+  if (!rc) rc = dev_alloc(d, &D.chan, nc);
+  if (!rc) rc = dev_alloc(d, &D.frame_off, nc * (size_t)(c.max_frames + 2));
+  if (!rc) rc = dev_alloc(d, &D.hist, nc * (size_t)D.hist_cap);
+  if (!rc) rc = dev_alloc(d, &D.lat, nc * (size_t)D.lat_cap);
+  d->per_channel_bytes = d->total_bytes / (int64_t)nc;
+  const int64_t before_lanes = d->total_bytes;
+  if (!rc) rc = dev_alloc(d, &D.slots, nl * (size_t)D.H);
+  if (!rc) rc = dev_alloc(d, &D.queue, nl * (size_t)D.qcap);
+  if (!rc) rc = dev_alloc(d, &D.aux, nl * (size_t)D.auxcap);
+  if (!rc) rc = dev_alloc(d, &D.dkey, nl * (size_t)D.tokcap);
+  if (!rc) rc = dev_alloc(d, &D.dslot, nl * (size_t)D.tokcap);
+  if (!rc) rc = dev_alloc(d, &d->d_params, nl);
+  d->per_lane_bytes = (d->total_bytes - before_lanes) / (int64_t)nl;
+  if (!rc) rc = dev_alloc(d, &d->d_chans, std::max(nc, nl));
+  if (!rc) rc = dev_alloc(d, &d->d_pathout, std::max(nc, nl));
+  if (!rc) rc = dev_alloc(d, &d->d_cnt, 1);
+  if (!rc) rc = dev_alloc(d, &d->d_offs, std::max(nc, nl) + 1);
+  if (!rc) {
+    bool ok = hipMemset(D.chan, 0, sizeof(ChanState) * nc) == hipSuccess;
+    for (int i = 0; ok && i < PARAM_RING; ++i)
+      ok = hipHostMalloc((void **)&d->h_params[i], sizeof(LaneParam) * nl) == hipSuccess &&
+           hipEventCreateWithFlags(&d->param_ev[i], hipEventDisableTiming) == hipSuccess;
+    if (ok) {
+      hipLaunchKernelGGL(k_fill_slots, dim3(1024), dim3(256), 0, 0, D.slots, nl * (size_t)D.H);
+      ok = hipGetLastError() == hipSuccess && hipDeviceSynchronize() == hipSuccess;
+    }
+    if (!ok) { (void)hipGetLastError(); rc = WFST_E_DEVICE; }
+  }
+  if (rc) { wfst_decode_destroy(d); return rc; }
+  d->inited.assign(nc, 0); d->frames_fed.assign(nc, 0); d->stamp.assign(nc, 0);
+  *out = d;
+  return 0;
+}
+
+void wfst_decode_destroy(wfst_decoder_t *d) {
+  if (!d) return;
+  (void)hipDeviceSynchronize();
+  for (void *p : d->allocs) (void)hipFree(p);
+  if (d->d_stage) (void)hipFree(d->d_stage);
+  for (int i = 0; i < PARAM_RING; ++i) {
+    if (d->h_params[i]) (void)hipHostFree(d->h_params[i]);
+    if (d->param_ev[i]) (void)hipEventDestroy(d->param_ev[i]);
+  }
+  for (auto &p : d->prof_events) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
+  delete d;
+}
+
+int wfst_decode_state_bytes(const wfst_decoder_t *d, int64_t *per_channel, int64_t *per_lane, int64_t *total) {
+  if (!d) return WFST_E_INVALID_ARG;
+  if (per_channel) *per_channel = d->per_channel_bytes;
+  if (per_lane) *per_lane = d->per_lane_bytes;
+  if (total) *total = d->total_bytes;
+  return 0;
+}
+
+int wfst_decode_init_channels(wfst_decoder_t *d, const int32_t *channels, int32_t n) {
+  if (!d || n < 0) return WFST_E_INVALID_ARG;
+  int rc = check_channels(d, channels, n, false);
+  if (rc) return rc;
+  std::vector<LaneParam> lp;
+  for (int32_t i = 0; i < n; i += d->cfg.max_lanes) {
+    const int32_t m = std::min(d->cfg.max_lanes, n - i);
+    lp.clear();
+    for (int32_t k = 0; k < m; ++k) lp.push_back(LaneParam{nullptr, channels[i + k], 1, 0, 0});
+    rc = launch_lanes(d, lp, 1, nullptr);
+    if (rc) return rc;
+  }
+  HIP_TRY(hipStreamSynchronize(nullptr));
+  for (int32_t i = 0; i < n; ++i) { d->inited[channels[i]] = 1; d->frames_fed[channels[i]] = 0; }
+  return 0;
+}
+
+int wfst_decode_free_channels(wfst_decoder_t *d, const int32_t *channels, int32_t n) {
+  if (!d || n < 0) return WFST_E_INVALID_ARG;
+  int rc = check_channels(d, channels, n, false);
+  if (rc) return rc;
+  for (int32_t i = 0; i < n; ++i) d->inited[channels[i]] = 0;
+  return 0;
+}
+
+int wfst_decode_advance(wfst_decoder_t *d, const int32_t *channels, int32_t n_lanes, const float *const *loglikes,
+                        const int32_t *strides, const int32_t *n_frames, void *stream) {
+  if (!d || n_lanes < 0 || n_lanes > d->cfg.max_lanes) return WFST_E_INVALID_ARG;
+  if (n_lanes == 0) return 0;
+  if (!loglikes || !strides || !n_frames) return WFST_E_INVALID_ARG;
+  int rc = check_channels(d, channels, n_lanes, true);
+  if (rc) return rc;
+  for (int32_t i = 0; i < n_lanes; ++i) {
+    if (n_frames[i] < 0 || strides[i] < d->dev.g.num_pdfs) return WFST_E_INVALID_ARG;
+    if (n_frames[i] > 0 && !loglikes[i]) return WFST_E_INVALID_ARG;
+    if (d->frames_fed[channels[i]] + n_frames[i] > d->cfg.max_frames) return WFST_E_HISTORY_OVERFLOW;
+  }
+  std::vector<LaneParam> lp((size_t)n_lanes);
+  for (int32_t i = 0; i < n_lanes; ++i) {
+    lp[i] = LaneParam{loglikes[i], channels[i], n_frames[i], strides[i], 0};
+    d->frames_fed[channels[i]] += n_frames[i];
+  }
+  return launch_lanes(d, lp, 0, (hipStream_t)stream);
+}
+
+int wfst_decode_best_path_batch(wfst_decoder_t *d, const int32_t *channels, int32_t n, int32_t use_final,
+                                int32_t *words, int32_t words_cap, int32_t *n_words, float *total_cost,
+                                int32_t *reached_final, int32_t *status) {
+  if (!d || n < 0 || words_cap < 0 || (n > 0 && (!n_words || !total_cost || !reached_final || !status))) return WFST_E_INVALID_ARG;
+  if (words_cap > 0 && !words && n > 0) return WFST_E_INVALID_ARG;
+  if (n == 0) return 0;
+  int rc = check_channels(d, channels, n, true);
+  if (rc) return rc;
+  HIP_TRY(hipDeviceSynchronize());
+  rc = ensure_stage(d, sizeof(int32_t) * (size_t)n * (size_t)std::max(words_cap, 1));
+  if (rc) return rc;
+  HIP_TRY(hipMemcpy(d->d_chans, channels, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
+  hipLaunchKernelGGL(k_best_path, dim3(n), dim3(64), 0, 0, d->dev, (const int32_t *)d->d_chans, use_final,
+                     words_cap > 0 ? (int32_t *)d->d_stage : nullptr, words_cap, (uint32_t *)nullptr, 0, d->d_pathout);
+  HIP_TRY(hipGetLastError());
+  std::vector<PathOut> po((size_t)n);
+  HIP_TRY(hipMemcpy(po.data(), d->d_pathout, sizeof(PathOut) * (size_t)n, hipMemcpyDeviceToHost));
+  std::vector<int32_t> w;
+  if (words_cap > 0) {
+    w.resize((size_t)n * (size_t)words_cap);
+    HIP_TRY(hipMemcpy(w.data(), d->d_stage, sizeof(int32_t) * w.size(), hipMemcpyDeviceToHost));
+  }
+  for (int32_t i = 0; i < n; ++i) {
+    status[i] = po[i].status; n_words[i] = po[i].n_words; total_cost[i] = po[i].total_cost; reached_final[i] = po[i].reached_final;
+    if (po[i].status == 0 && words_cap > 0 && po[i].n_words > 0)
+      std::memcpy(words + (size_t)i * words_cap, w.data() + (size_t)i * words_cap + (words_cap - po[i].n_words),
+                  sizeof(int32_t) * (size_t)po[i].n_words);
+    if (po[i].status == 0 && po[i].n_words > words_cap) status[i] = WFST_E_CAPACITY;
+  }
+  return 0;
+}
+
+int wfst_decode_best_path(wfst_decoder_t *d, int32_t channel, int32_t use_final, int32_t *words, int32_t cap,
+                          int32_t *n_words, float *total_cost, int32_t *reached_final) {
+  if (!n_words || !total_cost || !reached_final) return WFST_E_INVALID_ARG;
+  int32_t nw = 0, rf = 0, st = 0; float tc = 0.f;
+  int rc = wfst_decode_best_path_batch(d, &channel, 1, use_final, words, cap, &nw, &tc, &rf, &st);
+  if (rc) return rc;
+  if (st == WFST_E_CAPACITY) { *n_words = nw; return st; }
+  if (st) return st;
+  *n_words = nw; *total_cost = tc; *reached_final = rf;
+  return 0;
+}
+
+int wfst_decode_best_path_arcs(wfst_decoder_t *d, int32_t channel, int32_t use_final, uint32_t *arcs, int32_t cap,
+                               int32_t *n_arcs, float *total_cost, int32_t *reached_final) {
+  if (!d || cap < 0 || !n_arcs || !total_cost || !reached_final || (cap > 0 && !arcs)) return WFST_E_INVALID_ARG;
+  int rc = check_channels(d, &channel, 1, true);
+  if (rc) return rc;
+  HIP_TRY(hipDeviceSynchronize());
+  rc = ensure_stage(d, sizeof(uint32_t) * (size_t)std::max(cap, 1));
+  if (rc) return rc;
+  HIP_TRY(hipMemcpy(d->d_chans, &channel, sizeof(int32_t), hipMemcpyHostToDevice));
+  hipLaunchKernelGGL(k_best_path, dim3(1), dim3(64), 0, 0, d->dev, (const int32_t *)d->d_chans, use_final,
+                     (int32_t *)nullptr, 0, cap > 0 ? (uint32_t *)d->d_stage : nullptr, cap, d->d_pathout);
+  HIP_TRY(hipGetLastError());
+  PathOut po;
+  HIP_TRY(hipMemcpy(&po, d->d_pathout, sizeof(PathOut), hipMemcpyDeviceToHost));
+  if (po.status == 0 && po.n_arcs > cap) { *n_arcs = po.n_arcs; return WFST_E_CAPACITY; }
+  if (po.status) return po.status;
+  if (po.n_arcs > 0)
+    HIP_TRY(hipMemcpy(arcs, (uint32_t *)d->d_stage + (cap - po.n_arcs), sizeof(uint32_t) * (size_t)po.n_arcs, hipMemcpyDeviceToHost));
+  *n_arcs = po.n_arcs; *total_cost = po.total_cost; *reached_final = po.reached_final;
+  return 0;
+}
+
+static int read_chan(wfst_decoder *d, int32_t channel, ChanState *cs) {
+  HIP_TRY(hipDeviceSynchronize());
+  HIP_TRY(hipMemcpy(cs, d->dev.chan + channel, sizeof(ChanState), hipMemcpyDeviceToHost));
+  return 0;
+}
+
+int wfst_decode_lattice_arcs(wfst_decoder_t *d, int32_t channel, int32_t from_frame, wfst_lat_arc_t *out, int64_t cap,
+                             int64_t *n, int32_t out_is_device) {
+  if (!d || !n || cap < 0 || (cap > 0 && !out)) return WFST_E_INVALID_ARG;
+  int rc = check_channels(d, &channel, 1, true);
+  if (rc) return rc;
+  ChanState cs;
+  rc = read_chan(d, channel, &cs);
+  if (rc) return rc;
+  if (cs.status != 0 && cs.status != WFST_E_DEAD_CHANNEL && cs.status != WFST_E_NAN_INPUT) return cs.status;
+  const long long have = cs.lat_count;
+  rc = ensure_stage(d, sizeof(LatRec) * (size_t)std::max<long long>(have, 1));
+  if (rc) return rc;
+  HIP_TRY(hipMemset(d->d_cnt, 0, sizeof(unsigned long long)));
+  if (have > 0) {
+    const int blocks = (int)std::min<long long>((have + 255) / 256, 4096);
+    hipLaunchKernelGGL(k_export_lattice, dim3(blocks), dim3(256), 0, 0, d->dev, channel, have, from_frame,
+                       (LatRec *)d->d_stage, have, d->d_cnt);
+    HIP_TRY(hipGetLastError());
+  }
+  unsigned long long cnt = 0;
+  HIP_TRY(hipMemcpy(&cnt, d->d_cnt, sizeof(cnt), hipMemcpyDeviceToHost));
+  if ((int64_t)cnt > cap) { *n = (int64_t)cnt; return WFST_E_CAPACITY; }
+  if (cnt > 0)
+    HIP_TRY(hipMemcpy(out, d->d_stage, sizeof(LatRec) * (size_t)cnt, out_is_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost));
+  hipLaunchKernelGGL(k_reset_lattice, dim3(1), dim3(1), 0, 0, d->dev, channel);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipDeviceSynchronize());
+  *n = (int64_t)cnt;
+  return 0;
+}
+
+int wfst_decode_lattice_arcs_batch(wfst_decoder_t *d, const int32_t *channels, int32_t n, wfst_lat_arc_t *out,
+                                   int64_t cap, int64_t *offsets, int32_t out_is_device) {
+  if (!d || n < 0 || cap < 0 || !offsets || (cap > 0 && !out)) return WFST_E_INVALID_ARG;
+  offsets[0] = 0;
+  if (n == 0) return 0;
+  int rc = check_channels(d, channels, n, true);
+  if (rc) return rc;
+  HIP_TRY(hipDeviceSynchronize());
+  HIP_TRY(hipMemcpy(d->d_chans, channels, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
+  hipLaunchKernelGGL(k_lattice_counts, dim3((n + 255) / 256), dim3(256), 0, 0, d->dev, (const int32_t *)d->d_chans, n, d->d_offs);
+  HIP_TRY(hipGetLastError());
+  std::vector<long long> cnt((size_t)n), offs((size_t)n + 1);
+  HIP_TRY(hipMemcpy(cnt.data(), d->d_offs, sizeof(long long) * (size_t)n, hipMemcpyDeviceToHost));
+  offs[0] = 0;
+  for (int32_t i = 0; i < n; ++i) offs[i + 1] = offs[i] + cnt[i];
+  const long long total = offs[n];
+  for (int32_t i = 0; i <= n; ++i) offsets[i] = offs[i];
+  if (total > cap) return WFST_E_CAPACITY;
+  if (total > 0) {
+    LatRec *dst = (LatRec *)out;
+    if (!out_is_device) {
+      rc = ensure_stage(d, sizeof(LatRec) * (size_t)total);
+      if (rc) return rc;
+      dst = (LatRec *)d->d_stage;
+    }
+    HIP_TRY(hipMemcpy(d->d_offs, offs.data(), sizeof(long long) * ((size_t)n + 1), hipMemcpyHostToDevice));
+    hipLaunchKernelGGL(k_export_lattice_batch, dim3(n, 8), dim3(256), 0, 0, d->dev, (const int32_t *)d->d_chans,
+                       (const long long *)d->d_offs, dst);
+    HIP_TRY(hipGetLastError());
+    if (!out_is_device) HIP_TRY(hipMemcpy(out, dst, sizeof(LatRec) * (size_t)total, hipMemcpyDeviceToHost));
+  }
+  hipLaunchKernelGGL(k_reset_lattice_batch, dim3((n + 255) / 256), dim3(256), 0, 0, d->dev, (const int32_t *)d->d_chans, n);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipDeviceSynchronize());
+  return 0;
+}
+
+int wfst_decode_tokens(wfst_decoder_t *d, int32_t channel, int32_t frame, wfst_token_t *out, int32_t cap, int32_t *n) {
+  if (!d || !n || cap < 0 || (cap > 0 && !out)) return WFST_E_INVALID_ARG;
+  int rc = check_channels(d, &channel, 1, true);
+  if (rc) return rc;
+  ChanState cs;
+  rc = read_chan(d, channel, &cs);
+  if (rc) return rc;
+  if (frame < 0) frame += cs.num_frames;
+  if (frame < 0 || frame >= cs.num_frames) return WFST_E_INVALID_ARG;
+  long long off[2];
+  HIP_TRY(hipMemcpy(off, d->dev.frame_off + (size_t)channel * (size_t)(d->cfg.max_frames + 2) + frame, sizeof(off), hipMemcpyDeviceToHost));
+  const int cnt = (int)(off[1] - off[0]);
+  if (cnt > cap) { *n = cnt; return WFST_E_CAPACITY; }
+  if (cnt > 0) {
+    rc = ensure_stage(d, sizeof(TokOut) * (size_t)cnt);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_export_tokens, dim3((cnt + 255) / 256), dim3(256), 0, 0, d->dev, channel, off[0], cnt, (TokOut *)d->d_stage);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipMemcpy(out, d->d_stage, sizeof(TokOut) * (size_t)cnt, hipMemcpyDeviceToHost));
+  }
+  *n = cnt;
+  return 0;
+}
+
+int wfst_decode_stats(wfst_decoder_t *d, int32_t channel, wfst_stats_t *out) {
+  if (!d || !out) return WFST_E_INVALID_ARG;
+  int rc = check_channels(d, &channel, 1, true);
+  if (rc) return rc;
+  ChanState cs;
+  rc = read_chan(d, channel, &cs);
+  if (rc) return rc;
+  out->frames = cs.num_frames; out->arcs_expanded = cs.arcs_expanded; out->lattice_arcs = cs.lat_total;
+  out->max_tokens_pre_prune = cs.max_pre; out->max_tokens = cs.max_post; out->closure_iters_max = cs.closure_iters_max;
+  out->status = cs.status;
+  return 0;
+}
+
+int wfst_decode_set_profiling(wfst_decoder_t *d, int32_t on) {
+  if (!d) return WFST_E_INVALID_ARG;
+  d->profiling = on != 0;
+  return 0;
+}
+
+int wfst_decode_profile(wfst_decoder_t *d, int64_t *launches, double *total_ms) {
+  if (!d || !launches || !total_ms) return WFST_E_INVALID_ARG;
+  double ms = 0.0;
+  for (auto &p : d->prof_events) {
+    HIP_TRY(hipEventSynchronize(p.second));
+    float t = 0.f;
+    HIP_TRY(hipEventElapsedTime(&t, p.first, p.second));
+    ms += t;
+    (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second);
+  }
+  *launches = (int64_t)d->prof_events.size(); *total_ms = ms;
+  d->prof_events.clear();
+  return 0;
+}
+
+}  // extern "C"

@@ -1,0 +1,102 @@
+// Device-side data layout shared by the kernels and the host code of the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace wfst {
+
+// ---- graph ---------------------------------------------------------------------------
+// The graph is one array of 12-byte records (three 32-bit words).  State s owns a header
+// record followed by its emitting arcs and then its non-emitting arcs:
+//   header        {n_emit, n_eps, final cost bits}
+//   emitting arc  {dest handle | HAS_EPS, weight bits, pdf id}
+//   epsilon arc   {dest handle | HAS_EPS, weight bits, olabel}
+// A state's "handle" is the index of its header record, an arc's id on the device is the
+// index of its record.  Both grow with (state, emitting before epsilon, caller position),
+// so comparing record indices is comparing in that canonical arc order.  With the header
+// next to the arcs one cache line usually serves a whole state (direct indexing, as in the
+// paper's Section 3.2.1; 12 bytes per state and per arc is its Eq. 1 plus 4 bytes per
+// epsilon arc).
+constexpr uint32_t HAS_EPS = 0x80000000u;   // in a dest word: the destination has epsilon arcs
+constexpr uint32_t HMASK = 0x7FFFFFFFu;
+constexpr uint32_t NO_ARC = 0xFFFFFFFFu;
+constexpr uint32_t EMPTY = 0xFFFFFFFFu;     // empty hash slot
+
+struct GraphDev {
+  const uint32_t *rec;       // [3 * num_records]
+  const int32_t *label;      // [num_records] header: state id; arc: olabel        (readouts)
+  const uint32_t *orig;      // [num_records] arc: caller's arc id; header: NO_ARC (readouts)
+  uint32_t num_records;
+  uint32_t start_handle;
+  int32_t num_pdfs;
+};
+
+// ---- per-lane scratch ----------------------------------------------------------------
+// One open-addressing table per lane: FST state (handle) -> minimum packed candidate
+// (ordered cost bits << 32 | arc record index).
+struct __align__(16) Slot {
+  unsigned long long val;    // min packed candidate; ~0 when empty
+  uint32_t handle;           // EMPTY or the state handle
+  uint32_t aux;              // 0xFFFFFFFF fresh; bit 31 cleared once its epsilon arcs were
+                             // counted; after pruning: index in the new frame, or 0xFFFFFFFF
+};
+constexpr uint32_t AUX_GONE = 0x7FFFFFFFu;  // aux >= AUX_GONE: the token was not kept
+
+// queue entry: slot index | Q_EPS (state has epsilon arcs) | Q_DUP (re-expansion request)
+constexpr uint32_t Q_DUP = 0x80000000u;
+constexpr uint32_t Q_EPS = 0x40000000u;
+constexpr uint32_t Q_SLOT = 0x3FFFFFFFu;
+
+struct __align__(16) Aux {   // an emitting candidate that entered the table
+  uint32_t slot; float x; uint32_t arc; uint32_t src;
+};
+
+// ---- per-channel state ---------------------------------------------------------------
+struct __align__(16) HTok {  // one kept token of one frame
+  uint32_t handle;           // state handle | HAS_EPS
+  float cost;
+  uint32_t in_arc;           // record index of the best incoming arc, or NO_ARC
+  uint32_t prev;             // index of the source token: in the previous frame, or in this
+                             // frame when PREV_SAME is set; NO_ARC if unresolved / none
+};
+constexpr uint32_t PREV_SAME = 0x80000000u;
+
+struct LatRec { int32_t frame; uint32_t arc; float extra; };
+
+struct ChanState {
+  int32_t status;            // sticky error code (WFST_E_*) or 0
+  int32_t num_frames;        // token frames written (frame 0 comes from init)
+  long long hist_used;       // tokens in the history
+  long long lat_count;       // lattice records buffered
+  long long lat_total;       // lattice records produced since init
+  long long arcs_expanded;
+  int32_t max_pre, max_post, closure_iters_max, pad;
+};
+
+struct LaneParam {
+  const float *ll;           // device rows of this lane
+  int32_t chan, n_frames, stride, pad;
+};
+
+struct DecDev {
+  GraphDev g;
+  ChanState *chan;
+  long long *frame_off;      // [num_channels][max_frames + 2] start of each frame in hist
+  HTok *hist;                // [num_channels][hist_cap]
+  LatRec *lat;               // [num_channels][lat_cap]
+  Slot *slots;               // [max_lanes][H]
+  uint32_t *queue;           // [max_lanes][qcap]
+  Aux *aux;                  // [max_lanes][auxcap]
+  uint32_t *dkey;            // [max_lanes][tokcap] dense cost keys for the selection
+  uint32_t *dslot;           // [max_lanes][tokcap]
+  long long hist_cap, lat_cap;
+  uint32_t H;
+  int32_t hbits, qcap, auxcap, tokcap, max_frames, max_active, lattice_on;
+  float beam, lattice_beam;
+};
+
+// error codes mirrored from the public header (device code cannot include it cleanly)
+constexpr int E_TOKEN_OVERFLOW = -6, E_LATTICE_OVERFLOW = -7, E_DEAD_CHANNEL = -8, E_NAN_INPUT = -9,
+              E_BROKEN_TRACE = -10, E_HISTORY_OVERFLOW = -12, E_CAPACITY = -5;
+
+}  // namespace wfst

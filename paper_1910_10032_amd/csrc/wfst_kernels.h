@@ -1,0 +1,620 @@
+// Kernels of the decoder.
+//
+// One workgroup owns one lane (one audio stream of the batch) for a whole advance call and
+// loops over that lane's frames by itself: streams are independent and frames are strictly
+// serial (the paper's Section 3.1), so nothing ever has to be agreed between workgroups and
+// every synchronisation is a workgroup barrier.  This takes the paper's "one CTA per
+// utterance" persistent kernel for the tail of the non-emitting iterations (Section 3.3)
+// and applies it to the entire frame: with hundreds of lanes resident the chip is filled by
+// lanes rather than by the arcs of one lane, and no kernel launch sits between the stages
+// of Fig. 1.
+//
+// Per frame (Section 3, first paragraph; Fig. 1):
+//   1. emitting expansion, load-balanced over arcs (one thread per outgoing arc, Section
+//      3.3): x = (cost + weight) - loglike[pdf]; the lane's best cost is tracked in LDS and
+//      candidates within (running best + beam) enter the lane's state table through a
+//      64-bit atomic minimum over (ordered cost bits, arc index);
+//   2. non-emitting closure: rounds over the newly added / improved tokens until a round
+//      adds nothing;
+//   3. max-active: if more than max_active tokens are within the beam, an exact histogram
+//      selection over the ordered cost bits (then over state handles among ties) finds the
+//      cut; its cost is the frame's effective cutoff (the adaptive beam);
+//   4. contraction: the kept tokens are appended to the channel's token history, which is
+//      also the queue the next frame expands from;
+//   5. lattice preprocessing (Section 3.4): every candidate arc that reaches a kept token
+//      within the effective cutoff and the lattice beam is recorded with its extra cost;
+//      the arc equal to the table's minimum fixes the token's back-pointer;
+//   6. the touched table slots are cleared.
+#pragma once
+#include "wfst_device.h"
+
+namespace wfst {
+
+constexpr int NBINS = 2048;
+constexpr uint32_t F_NAN = 1, F_TOKOVF = 2, F_LATOVF = 4;
+constexpr uint32_t KEY_NONE = 0xFFFFFFFFu;
+constexpr uint32_t KEY_PINF = 0xFF800000u;    // okey(+inf)
+
+__device__ __forceinline__ uint32_t okey(float x) {
+  uint32_t b = __float_as_uint(x);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float key2f(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+__device__ __forceinline__ unsigned long long pack(uint32_t key, uint32_t arc) {
+  return ((unsigned long long)key << 32) | arc;
+}
+// Loads that bypass the per-CU vector cache: table words are updated by atomics, which
+// execute in L2, so cached copies could be stale.
+__device__ __forceinline__ uint32_t ld32(const uint32_t *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long ld64(const unsigned long long *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t slot_hash(uint32_t handle, int hbits) {
+  return (handle * 2654435761u) >> (32 - hbits);
+}
+
+// Offer candidate K for state `handle`.  Returns the slot, or -1 if the table is full.
+__device__ __forceinline__ int ht_insert(Slot *slots, uint32_t mask, int hbits, uint32_t handle,
+                                         unsigned long long K, bool &claimed, bool &improved) {
+  uint32_t h = slot_hash(handle, hbits);
+  claimed = false; improved = false;
+  for (uint32_t probe = 0; probe <= mask; ++probe) {
+    uint32_t k = ld32(&slots[h].handle);
+    if (k == EMPTY) {
+      k = atomicCAS(&slots[h].handle, EMPTY, handle);
+      if (k == EMPTY) { claimed = true; k = handle; }
+    }
+    if (k == handle) {
+      unsigned long long old = atomicMin(&slots[h].val, K);
+      improved = K < old;
+      return (int)h;
+    }
+    h = (h + 1) & mask;
+  }
+  return -1;
+}
+__device__ __forceinline__ int ht_find(const Slot *slots, uint32_t mask, int hbits, uint32_t handle) {
+  uint32_t h = slot_hash(handle, hbits);
+  for (uint32_t probe = 0; probe <= mask; ++probe) {
+    uint32_t k = ld32(&slots[h].handle);
+    if (k == handle) return (int)h;
+    if (k == EMPTY) return -1;
+    h = (h + 1) & mask;
+  }
+  return -1;
+}
+
+template <int NT>
+struct LaneShared {
+  int wave_tmp[NT / 64];
+  int scan[NT];
+  float cost[NT];
+  uint32_t base[NT];
+  uint32_t hist[NBINS];
+  uint32_t qtail, nclaim, auxn, best, flags, nvalid, nout, latn, kmin, kmax;
+  uint32_t sel_bin, sel_below, sel_cnt;
+  unsigned long long emit_arcs, eps_arcs;
+  // channel state, cached for the duration of the call
+  int status, nf, max_pre, max_post, iters_max;
+  long long hist_used, lat_count, lat_total, arcs_expanded;
+};
+
+template <int NT>
+__device__ __forceinline__ int block_excl_scan(int v, int *s_wave, int &total) {
+  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    int t = __shfl_up(inc, d, 64);
+    if (lane >= d) inc += t;
+  }
+  if (lane == 63) s_wave[wid] = inc;
+  __syncthreads();
+  int base = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < NT / 64; ++i) {
+    int t = s_wave[i];
+    if (i < wid) base += t;
+    tot += t;
+  }
+  __syncthreads();
+  total = tot;
+  return base + inc - v;
+}
+
+// The need-th smallest (1-based) of the values val(i, v) accepts, all known to lie in
+// [lo, hi]: theta, with the number of accepted values below it and equal to it.  Exact:
+// only integer histograms, refined until a bin is one value wide.
+template <int NT, class F>
+__device__ void block_select(LaneShared<NT> &S, int n, uint32_t need, uint32_t lo, uint32_t hi, F val,
+                             uint32_t &theta, uint32_t &n_less, uint32_t &n_eq) {
+  const int tid = threadIdx.x;
+  constexpr int PER = NBINS / NT;
+  uint32_t less = 0;
+  for (;;) {
+    unsigned long long range = (unsigned long long)hi - lo + 1;
+    int shift = 0;
+    while ((range >> shift) > (unsigned long long)NBINS) ++shift;
+    for (int b = tid; b < NBINS; b += NT) S.hist[b] = 0;
+    __syncthreads();
+    for (int i = tid; i < n; i += NT) {
+      uint32_t v;
+      if (val(i, v) && v >= lo && v <= hi) atomicAdd(&S.hist[(v - lo) >> shift], 1u);
+    }
+    __syncthreads();
+    uint32_t loc[PER], sum = 0;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) { loc[q] = S.hist[tid * PER + q]; sum += loc[q]; }
+    int total;
+    uint32_t run = (uint32_t)block_excl_scan<NT>((int)sum, S.wave_tmp, total);
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      if (run < need && run + loc[q] >= need) { S.sel_bin = tid * PER + q; S.sel_below = run; S.sel_cnt = loc[q]; }
+      run += loc[q];
+    }
+    __syncthreads();
+    const uint32_t b = S.sel_bin, below = S.sel_below, cnt = S.sel_cnt;
+    __syncthreads();
+    less += below;
+    need -= below;
+    lo = lo + (b << shift);
+    unsigned long long nhi = (unsigned long long)lo + ((1ull << shift) - 1);
+    if (nhi < hi) hi = (uint32_t)nhi;
+    if (shift == 0) { theta = lo; n_less = less; n_eq = cnt; return; }
+  }
+}
+
+template <int NT>
+__device__ void lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &lp, const float *ll, bool is_init,
+                           Slot *slots, uint32_t *queue, Aux *aux, uint32_t *dkey, uint32_t *dslot,
+                           long long *foff, HTok *hist, LatRec *lat) {
+  const int tid = threadIdx.x;
+  const uint32_t *rec = D.g.rec;
+  const uint32_t mask = D.H - 1;
+  const int hbits = D.hbits;
+
+  if (tid == 0) {
+    S.qtail = 0; S.nclaim = 0; S.auxn = 0; S.best = KEY_NONE; S.flags = 0; S.nvalid = 0; S.nout = 0; S.latn = 0;
+    S.kmin = 0xFFFFFFFFu; S.kmax = 0; S.emit_arcs = 0; S.eps_arcs = 0;
+  }
+  __syncthreads();
+  const int nf = S.nf;                       // index of the frame being written
+  const long long out_base = S.hist_used;
+  int abort_code = 0;
+  if (nf > D.max_frames) abort_code = E_HISTORY_OVERFLOW;
+
+  // ---- 1. emitting expansion ------------------------------------------------------------
+  if (abort_code == 0) {
+    if (is_init) {
+      if (tid == 0) {
+        const uint32_t h = D.g.start_handle;
+        bool cl, im;
+        int sl = ht_insert(slots, mask, hbits, h, pack(okey(0.0f), NO_ARC), cl, im);
+        queue[0] = (uint32_t)sl | (rec[3 * (size_t)h + 1] ? Q_EPS : 0u);
+        S.qtail = 1; S.nclaim = 1; S.best = okey(0.0f);
+      }
+    } else {
+      const long long in_off = foff[nf - 1];
+      const int n_in = (int)(foff[nf] - in_off);
+      for (int tb = 0; tb < n_in; tb += NT) {
+        const int i = tb + tid;
+        int ne = 0; uint32_t h = 0; float c = 0.f;
+        if (i < n_in) {
+          const HTok t = hist[in_off + i];
+          h = t.handle & HMASK; c = t.cost;
+          ne = (int)rec[3 * (size_t)h];
+        }
+        int total;
+        const int ex = block_excl_scan<NT>(ne, S.wave_tmp, total);
+        S.scan[tid] = ex; S.cost[tid] = c; S.base[tid] = h + 1;
+        __syncthreads();
+        if (tid == 0) S.emit_arcs += (unsigned long long)total;
+        for (int j0 = 0; j0 < total; j0 += NT) {
+          const int j = j0 + tid;
+          const bool act = j < total;
+          float x = 0.f; uint32_t r = 0, dw = 0, kx = KEY_NONE; int k = 0;
+          if (act) {
+            int lo = 0, hi = NT - 1;             // largest k with scan[k] <= j
+            while (lo < hi) { int mid = (lo + hi + 1) >> 1; if (S.scan[mid] <= j) lo = mid; else hi = mid - 1; }
+            k = lo;
+            r = S.base[k] + (uint32_t)(j - S.scan[k]);
+            const uint32_t *a = rec + 3 * (size_t)r;
+            dw = a[0];
+            const float w = __uint_as_float(a[1]);
+            const float llv = ll[a[2]];
+            const float cw = S.cost[k] + w;
+            x = cw - llv;
+            if (x != x || x == -INFINITY) atomicOr(&S.flags, F_NAN); else kx = okey(x);
+          }
+          uint32_t m = kx;
+#pragma unroll
+          for (int d = 32; d; d >>= 1) m = min(m, (uint32_t)__shfl_xor((int)m, d, 64));
+          if ((tid & 63) == 0 && m != KEY_NONE) atomicMin(&S.best, m);
+          __syncthreads();
+          const float cut = key2f(S.best) + D.beam;     // running bound, never below the final cutoff
+          if (act && kx != KEY_NONE && x <= cut) {
+            bool cl, im;
+            const int sl = ht_insert(slots, mask, hbits, dw & HMASK, pack(kx, r), cl, im);
+            if (sl < 0) atomicOr(&S.flags, F_TOKOVF);
+            else {
+              if (cl) {
+                const uint32_t ci = atomicAdd(&S.nclaim, 1u), q = atomicAdd(&S.qtail, 1u);
+                if (ci >= (uint32_t)D.tokcap || q >= (uint32_t)D.qcap) atomicOr(&S.flags, F_TOKOVF);
+                else queue[q] = (uint32_t)sl | ((dw & HAS_EPS) ? Q_EPS : 0u);
+              }
+              if (D.lattice_on || im) {
+                const uint32_t ai = atomicAdd(&S.auxn, 1u);
+                if (ai >= (uint32_t)D.auxcap) atomicOr(&S.flags, F_LATOVF);
+                else aux[ai] = Aux{(uint32_t)sl, x, r, (uint32_t)(tb + k)};
+              }
+            }
+          }
+        }
+        __syncthreads();
+      }
+    }
+  }
+  __syncthreads();
+  const uint32_t bestk = S.best;
+  if (abort_code == 0) {
+    const uint32_t fl = S.flags;
+    if (fl & F_NAN) abort_code = E_NAN_INPUT;
+    else if (fl & F_TOKOVF) abort_code = E_TOKEN_OVERFLOW;
+    else if (fl & F_LATOVF) abort_code = E_LATTICE_OVERFLOW;
+    else if (bestk == KEY_NONE || bestk == KEY_PINF) abort_code = E_DEAD_CHANNEL;
+  }
+  const float cutoff = key2f(bestk) + D.beam;
+
+  // ---- 2. non-emitting closure ----------------------------------------------------------
+  int iters = 0;
+  if (abort_code == 0) {
+    uint32_t w0 = 0, w1 = min(S.qtail, (uint32_t)D.qcap);
+    __syncthreads();
+    while (w0 < w1) {
+      for (uint32_t i = w0 + tid; i < w1; i += NT) {
+        const uint32_t e = queue[i];
+        if (!(e & Q_EPS)) continue;
+        Slot *sp = slots + (e & Q_SLOT);
+        const float c = key2f((uint32_t)(ld64(&sp->val) >> 32));
+        if (!(c <= cutoff)) continue;
+        const uint32_t h = ld32(&sp->handle);
+        const uint32_t ne = rec[3 * (size_t)h], np = rec[3 * (size_t)h + 1];
+        if (atomicAnd(&sp->aux, 0x7FFFFFFFu) >> 31) atomicAdd(&S.eps_arcs, (unsigned long long)np);
+        for (uint32_t k = 0; k < np; ++k) {
+          const uint32_t r = h + 1 + ne + k;
+          const uint32_t *a = rec + 3 * (size_t)r;
+          const uint32_t dw = a[0];
+          const float x = c + __uint_as_float(a[1]);
+          if (!(x <= cutoff)) continue;
+          bool cl, im;
+          const int sl = ht_insert(slots, mask, hbits, dw & HMASK, pack(okey(x), r), cl, im);
+          if (sl < 0) { atomicOr(&S.flags, F_TOKOVF); continue; }
+          if (cl || im) {
+            if (cl && atomicAdd(&S.nclaim, 1u) >= (uint32_t)D.tokcap) atomicOr(&S.flags, F_TOKOVF);
+            const uint32_t q = atomicAdd(&S.qtail, 1u);
+            if (q >= (uint32_t)D.qcap) atomicOr(&S.flags, F_TOKOVF);
+            else queue[q] = (uint32_t)sl | ((dw & HAS_EPS) ? Q_EPS : 0u) | (cl ? 0u : Q_DUP);
+          }
+        }
+      }
+      __syncthreads();
+      w0 = w1; w1 = min(S.qtail, (uint32_t)D.qcap);
+      ++iters;
+      __syncthreads();
+    }
+    if (S.flags & F_TOKOVF) abort_code = E_TOKEN_OVERFLOW;
+  }
+  const uint32_t n_q = min(S.qtail, (uint32_t)D.qcap);
+
+  // ---- 3 + 4. max-active selection and contraction into the token history ---------------
+  float cutoff_eff = cutoff;
+  if (abort_code == 0) {
+    const uint32_t nclaim = S.nclaim;
+    const uint32_t room = (uint32_t)min((long long)0x7FFFFFFF, D.hist_cap - out_base);
+    if (min(nclaim, (uint32_t)D.max_active) > room) abort_code = E_HISTORY_OVERFLOW;
+    else if (nclaim <= (uint32_t)D.max_active) {
+      // nothing can be pruned: every token within the beam is kept
+      for (uint32_t i = tid; i < n_q; i += NT) {
+        const uint32_t e = queue[i];
+        if (e & Q_DUP) continue;
+        Slot *sp = slots + (e & Q_SLOT);
+        const unsigned long long v = ld64(&sp->val);
+        const float c = key2f((uint32_t)(v >> 32));
+        if (!(c <= cutoff)) continue;
+        const uint32_t pos = atomicAdd(&S.nout, 1u);
+        if (pos >= room) continue;
+        hist[out_base + pos] = HTok{ld32(&sp->handle) | ((e & Q_EPS) ? HAS_EPS : 0u), c, (uint32_t)v, NO_ARC};
+        sp->aux = pos;
+      }
+      __syncthreads();
+      if (tid == 0) S.nvalid = S.nout;
+    } else {
+      for (uint32_t i = tid; i < n_q; i += NT) {
+        const uint32_t e = queue[i];
+        if (e & Q_DUP) continue;
+        const uint32_t key = (uint32_t)(ld64(&slots[e & Q_SLOT].val) >> 32);
+        if (!(key2f(key) <= cutoff)) continue;
+        const uint32_t p = atomicAdd(&S.nvalid, 1u);
+        dkey[p] = key; dslot[p] = e & (Q_SLOT | Q_EPS);
+        atomicMin(&S.kmin, key); atomicMax(&S.kmax, key);
+      }
+      __syncthreads();
+      const int n = (int)S.nvalid;
+      uint32_t theta = KEY_NONE, h_theta = 0xFFFFFFFFu;       // keep key < theta, or == theta with handle <= h_theta
+      if (n > D.max_active) {
+        uint32_t n_less, n_eq;
+        block_select<NT>(S, n, (uint32_t)D.max_active, S.kmin, S.kmax,
+                         [&](int i, uint32_t &v) { v = dkey[i]; return true; }, theta, n_less, n_eq);
+        const uint32_t need_eq = (uint32_t)D.max_active - n_less;
+        if (need_eq < n_eq) {
+          uint32_t hl, he;
+          block_select<NT>(S, n, need_eq, 0u, HMASK,
+                           [&](int i, uint32_t &v) {
+                             if (dkey[i] != theta) return false;
+                             v = ld32(&slots[dslot[i] & Q_SLOT].handle);
+                             return true;
+                           }, h_theta, hl, he);
+        }
+        cutoff_eff = key2f(theta);
+      }
+      for (int i = tid; i < n; i += NT) {
+        const uint32_t key = dkey[i], ds = dslot[i];
+        Slot *sp = slots + (ds & Q_SLOT);
+        const uint32_t h = ld32(&sp->handle);
+        const bool keep = key < theta || (key == theta && h <= h_theta);
+        uint32_t pos = 0xFFFFFFFFu;
+        if (keep) pos = atomicAdd(&S.nout, 1u);
+        if (pos < room) {
+          hist[out_base + pos] = HTok{h | ((ds & Q_EPS) ? HAS_EPS : 0u), key2f(key), (uint32_t)ld64(&sp->val), NO_ARC};
+          sp->aux = pos;
+        } else {
+          sp->aux = 0xFFFFFFFFu;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  const uint32_t n_out = (abort_code == 0) ? min(S.nout, (uint32_t)D.max_active) : 0u;
+
+  // ---- 5. lattice records and back-pointers ---------------------------------------------
+  if (abort_code == 0) {
+    const long long lat_base = S.lat_count;
+    const uint32_t n_aux = min(S.auxn, (uint32_t)D.auxcap);
+    auto emit_lat = [&](uint32_t arc, float extra) {
+      const uint32_t p = atomicAdd(&S.latn, 1u);
+      if (lat_base + (long long)p >= D.lat_cap) atomicOr(&S.flags, F_LATOVF);
+      else lat[lat_base + p] = LatRec{nf, arc, extra};
+    };
+    for (uint32_t i = tid; i < n_aux; i += NT) {
+      const Aux a = aux[i];
+      const Slot *sp = slots + a.slot;
+      const uint32_t pos = ld32(&sp->aux);
+      if (pos >= AUX_GONE) continue;
+      const unsigned long long v = ld64(&sp->val);
+      if (pack(okey(a.x), a.arc) == v) hist[out_base + pos].prev = a.src;
+      if (D.lattice_on && a.x <= cutoff_eff) {
+        const float extra = a.x - key2f((uint32_t)(v >> 32));
+        if (extra <= D.lattice_beam) emit_lat(a.arc, extra);
+      }
+    }
+    for (uint32_t j = tid; j < n_out; j += NT) {
+      const HTok t = hist[out_base + j];
+      if (!(t.handle & HAS_EPS)) continue;
+      const uint32_t h = t.handle & HMASK;
+      const uint32_t ne = rec[3 * (size_t)h], np = rec[3 * (size_t)h + 1];
+      for (uint32_t k = 0; k < np; ++k) {
+        const uint32_t r = h + 1 + ne + k;
+        const uint32_t *a = rec + 3 * (size_t)r;
+        const float x = t.cost + __uint_as_float(a[1]);
+        if (!(x <= cutoff_eff)) continue;
+        const int sl = ht_find(slots, mask, hbits, a[0] & HMASK);
+        if (sl < 0) continue;
+        const Slot *sp = slots + sl;
+        const uint32_t pos = ld32(&sp->aux);
+        if (pos >= AUX_GONE) continue;
+        const unsigned long long v = ld64(&sp->val);
+        if (pack(okey(x), r) == v) hist[out_base + pos].prev = j | PREV_SAME;
+        if (D.lattice_on) {
+          const float extra = x - key2f((uint32_t)(v >> 32));
+          if (extra <= D.lattice_beam) emit_lat(r, extra);
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- 6. clear the table ---------------------------------------------------------------
+  const Slot fresh{~0ull, EMPTY, 0xFFFFFFFFu};
+  if (S.flags & F_TOKOVF) {
+    for (uint32_t i = tid; i < D.H; i += NT) slots[i] = fresh;      // untracked claims: wipe everything
+  } else {
+    for (uint32_t i = tid; i < n_q; i += NT) {
+      const uint32_t e = queue[i];
+      if (!(e & Q_DUP)) slots[e & Q_SLOT] = fresh;
+    }
+  }
+  if (tid == 0) {
+    if (abort_code == 0 && (S.flags & F_LATOVF)) abort_code = E_LATTICE_OVERFLOW;
+    const long long lat_new = min((long long)S.latn, max(0ll, D.lat_cap - S.lat_count));
+    if (nf <= D.max_frames) {
+      foff[nf + 1] = out_base + n_out;
+      S.nf = nf + 1;
+    }
+    S.hist_used = out_base + n_out;
+    S.lat_count += lat_new; S.lat_total += lat_new;
+    S.arcs_expanded += (long long)(S.emit_arcs + S.eps_arcs);
+    S.max_pre = max(S.max_pre, (int)S.nvalid);
+    S.max_post = max(S.max_post, (int)n_out);
+    S.iters_max = max(S.iters_max, iters);
+    if (abort_code != 0) S.status = abort_code;
+  }
+  __syncthreads();
+}
+
+// One workgroup per lane.  is_init: (re)start the lane's channel and write frame 0.
+template <int NT>
+__global__ void __launch_bounds__(NT) k_advance(DecDev D, const LaneParam *__restrict__ lanes, int is_init) {
+  __shared__ LaneShared<NT> S;
+  const int tid = threadIdx.x;
+  const LaneParam lp = lanes[blockIdx.x];
+  ChanState *cs = D.chan + lp.chan;
+  Slot *slots = D.slots + (size_t)blockIdx.x * D.H;
+  uint32_t *queue = D.queue + (size_t)blockIdx.x * (size_t)D.qcap;
+  Aux *aux = D.aux + (size_t)blockIdx.x * (size_t)D.auxcap;
+  uint32_t *dkey = D.dkey + (size_t)blockIdx.x * (size_t)D.tokcap;
+  uint32_t *dslot = D.dslot + (size_t)blockIdx.x * (size_t)D.tokcap;
+  long long *foff = D.frame_off + (size_t)lp.chan * (size_t)(D.max_frames + 2);
+  HTok *hist = D.hist + (size_t)lp.chan * (size_t)D.hist_cap;
+  LatRec *lat = D.lat + (size_t)lp.chan * (size_t)D.lat_cap;
+
+  if (tid == 0) {
+    if (is_init) {
+      S.status = 0; S.nf = 0; S.hist_used = 0; S.lat_count = 0; S.lat_total = 0; S.arcs_expanded = 0;
+      S.max_pre = 0; S.max_post = 0; S.iters_max = 0;
+      foff[0] = 0;
+    } else {
+      S.status = cs->status; S.nf = cs->num_frames; S.hist_used = cs->hist_used; S.lat_count = cs->lat_count;
+      S.lat_total = cs->lat_total; S.arcs_expanded = cs->arcs_expanded; S.max_pre = cs->max_pre;
+      S.max_post = cs->max_post; S.iters_max = cs->closure_iters_max;
+    }
+  }
+  __syncthreads();
+  const int nframes = is_init ? 1 : lp.n_frames;
+  for (int f = 0; f < nframes; ++f) {
+    if (S.status != 0) break;
+    lane_frame<NT>(D, S, lp, is_init ? nullptr : lp.ll + (size_t)f * (size_t)lp.stride, is_init != 0,
+                   slots, queue, aux, dkey, dslot, foff, hist, lat);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    cs->status = S.status; cs->num_frames = S.nf; cs->hist_used = S.hist_used; cs->lat_count = S.lat_count;
+    cs->lat_total = S.lat_total; cs->arcs_expanded = S.arcs_expanded; cs->max_pre = S.max_pre;
+    cs->max_post = S.max_post; cs->closure_iters_max = S.iters_max;
+  }
+}
+
+__global__ void k_fill_slots(Slot *slots, size_t n) {
+  const Slot fresh{~0ull, EMPTY, 0xFFFFFFFFu};
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) slots[i] = fresh;
+}
+
+// ---- readouts ----------------------------------------------------------------------------
+struct PathOut { int32_t status, n_words, n_arcs, reached_final; float total_cost; };
+
+// One wave per requested channel: arg-min over the last frame, then one lane follows the
+// back-pointers.  Words / arcs are written right-aligned into the channel's cap-sized
+// region, so a single backward walk leaves them in path order.
+__global__ void __launch_bounds__(64) k_best_path(DecDev D, const int32_t *chans, int use_final,
+                                                  int32_t *words, int words_cap, uint32_t *arcs, int arcs_cap,
+                                                  PathOut *out) {
+  const int ch = chans[blockIdx.x];
+  const int lane = threadIdx.x;
+  const ChanState *cs = D.chan + ch;
+  const long long *foff = D.frame_off + (size_t)ch * (size_t)(D.max_frames + 2);
+  const HTok *hist = D.hist + (size_t)ch * (size_t)D.hist_cap;
+  const uint32_t *rec = D.g.rec;
+  PathOut po{0, 0, 0, 0, 0.f};
+  if (cs->status != 0) { if (lane == 0) { po.status = cs->status; out[blockIdx.x] = po; } return; }
+  const int F = cs->num_frames - 1;
+  const long long o = foff[F];
+  const int n = (int)(foff[F + 1] - o);
+  // packed (ordered cost, handle) minimum; final states first if asked for
+  unsigned long long bf = ~0ull, bn = ~0ull; int bfi = -1, bni = -1;
+  for (int i = lane; i < n; i += 64) {
+    const HTok t = hist[o + i];
+    const uint32_t h = t.handle & HMASK;
+    const unsigned long long kn = pack(okey(t.cost), h);
+    if (kn < bn) { bn = kn; bni = i; }
+    if (use_final) {
+      const float fc = __uint_as_float(rec[3 * (size_t)h + 2]);
+      if (fc != INFINITY) {
+        const unsigned long long kf = pack(okey(t.cost + fc), h);
+        if (kf < bf) { bf = kf; bfi = i; }
+      }
+    }
+  }
+  for (int d = 32; d; d >>= 1) {
+    unsigned long long o2 = __shfl_xor(bn, d, 64); int i2 = __shfl_xor(bni, d, 64);
+    if (o2 < bn) { bn = o2; bni = i2; }
+    o2 = __shfl_xor(bf, d, 64); i2 = __shfl_xor(bfi, d, 64);
+    if (o2 < bf) { bf = o2; bfi = i2; }
+  }
+  if (lane != 0) return;
+  if (n == 0) { po.status = E_DEAD_CHANNEL; out[blockIdx.x] = po; return; }
+  int cur;
+  if (use_final && bfi >= 0) { cur = bfi; po.total_cost = key2f((uint32_t)(bf >> 32)); po.reached_final = 1; }
+  else { cur = bni; po.total_cost = key2f((uint32_t)(bn >> 32)); }
+  int32_t *wout = words ? words + (size_t)blockIdx.x * words_cap : nullptr;
+  uint32_t *aout = arcs ? arcs + (size_t)blockIdx.x * arcs_cap : nullptr;
+  int f = F, nw = 0, na = 0;
+  const long long max_steps = cs->hist_used + 1;
+  for (long long step = 0;; ++step) {
+    if (cur < 0 || (long long)cur >= foff[f + 1] - foff[f]) { po.status = E_BROKEN_TRACE; break; }
+    const HTok t = hist[foff[f] + cur];
+    if (t.in_arc == NO_ARC) break;
+    if (t.prev == NO_ARC || step > max_steps) { po.status = E_BROKEN_TRACE; break; }
+    if (aout && na < arcs_cap) aout[arcs_cap - 1 - na] = D.g.orig[t.in_arc];
+    ++na;
+    const int32_t w = D.g.label[t.in_arc];
+    if (w != 0) { if (wout && nw < words_cap) wout[words_cap - 1 - nw] = w; ++nw; }
+    if (t.prev & PREV_SAME) cur = (int)(t.prev & ~PREV_SAME);
+    else { cur = (int)t.prev; --f; if (f < 0) { po.status = E_BROKEN_TRACE; break; } }
+  }
+  po.n_words = nw; po.n_arcs = na;
+  if (po.status == 0 && ((wout && nw > words_cap) || (aout && na > arcs_cap))) po.status = E_CAPACITY;
+  out[blockIdx.x] = po;
+}
+
+// Tokens of one frame in the public form: state id and caller's arc id.
+struct TokOut { int32_t state; float cost; uint32_t in_arc; };
+__global__ void k_export_tokens(DecDev D, int ch, long long off, int n, TokOut *out) {
+  const HTok *hist = D.hist + (size_t)ch * (size_t)D.hist_cap;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    const HTok t = hist[off + i];
+    out[i] = TokOut{D.g.label[t.handle & HMASK], t.cost, t.in_arc == NO_ARC ? NO_ARC : D.g.orig[t.in_arc]};
+  }
+}
+
+// Lattice records with frame >= from_frame, arc ids translated to the caller's; cnt is
+// the running output count (zeroed by the host).
+__global__ void k_export_lattice(DecDev D, int ch, long long n, int from_frame, LatRec *out, long long cap,
+                                 unsigned long long *cnt) {
+  const LatRec *lat = D.lat + (size_t)ch * (size_t)D.lat_cap;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) {
+    const LatRec r = lat[i];
+    if (r.frame < from_frame) continue;
+    const unsigned long long p = atomicAdd(cnt, 1ull);
+    if ((long long)p < cap) out[p] = LatRec{r.frame, D.g.orig[r.arc], r.extra};
+  }
+}
+__global__ void k_reset_lattice(DecDev D, int ch) { D.chan[ch].lat_count = 0; }
+
+// Batched drain: counts of the listed channels, then one copy kernel (grid.x = channel,
+// grid.y = slices of that channel's buffer), then the reset.
+__global__ void k_lattice_counts(DecDev D, const int32_t *chans, int n, long long *counts) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) {
+    const ChanState *cs = D.chan + chans[i];
+    const bool readable = cs->status == 0 || cs->status == E_DEAD_CHANNEL || cs->status == E_NAN_INPUT;
+    counts[i] = readable ? cs->lat_count : 0;
+  }
+}
+__global__ void k_export_lattice_batch(DecDev D, const int32_t *chans, const long long *offs, LatRec *out) {
+  const int ch = chans[blockIdx.x];
+  const LatRec *lat = D.lat + (size_t)ch * (size_t)D.lat_cap;
+  const long long o = offs[blockIdx.x], n = offs[blockIdx.x + 1] - o;
+  for (long long i = (long long)blockIdx.y * blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.y * blockDim.x) {
+    const LatRec r = lat[i];
+    out[o + i] = LatRec{r.frame, D.g.orig[r.arc], r.extra};
+  }
+}
+__global__ void k_reset_lattice_batch(DecDev D, const int32_t *chans, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) D.chan[chans[i]].lat_count = 0;
+}
+
+}  // namespace wfst

@@ -66,7 +66,7 @@ static int draw_degrees(const synth_graph_spec *sp, int32_t *deg, int64_t *total
   const int32_t Q = sp->num_states;
   const int32_t dmax = sp->deg_max > 0 ? sp->deg_max : 1;
   double *cdf = NULL;
-  double p_zero = 0.0;
+  double p_one = 0.0;
   if (sp->degree_model == 2) {
     cdf = (double *)malloc(sizeof(double) * (size_t)dmax);
     if (!cdf) return -1;
@@ -77,7 +77,9 @@ static int draw_degrees(const synth_graph_spec *sp, int32_t *deg, int64_t *total
     double mean = m / z;
     if (sp->num_emit > 0) {
       double want = (double)sp->num_emit / (double)Q;
-      if (want < mean) p_zero = 1.0 - want / mean;   /* mix in states without emitting arcs */
+      /* the pure power law has a larger mean than asked for: mix in states with exactly one
+         emitting arc (never zero: like a real decoding graph, every state can move on) */
+      if (want < mean && mean > 1.0) p_one = (mean - want) / (mean - 1.0);
     }
   }
   int64_t total = 0;
@@ -90,8 +92,8 @@ static int draw_degrees(const synth_graph_spec *sp, int32_t *deg, int64_t *total
       double u = 1.0 - u01(h3(sp->seed, TAG_DEG, (uint64_t)s));      /* (0,1] */
       d = 1 + (int32_t)floor(log(u) / log(q));
     } else {
-      if (u01(h3(sp->seed, TAG_ZERO, (uint64_t)s)) < p_zero) {
-        d = 0;
+      if (u01(h3(sp->seed, TAG_ZERO, (uint64_t)s)) < p_one) {
+        d = 1;
       } else {
         double u = u01(h3(sp->seed, TAG_DEG, (uint64_t)s));
         int lo = 0, hi = dmax - 1;                                    /* first k with cdf >= u */
@@ -116,7 +118,7 @@ static int draw_degrees(const synth_graph_spec *sp, int32_t *deg, int64_t *total
     uint64_t i = 0;
     while (total != sp->num_emit) {
       int32_t s = (int32_t)(h3(sp->seed, TAG_ADJ, i++) % (uint64_t)Q);
-      if (total > sp->num_emit) { if (s != 0 && deg[s] > 0) { deg[s]--; total--; } }
+      if (total > sp->num_emit) { if (s != 0 && deg[s] > 1) { deg[s]--; total--; } }
       else if (deg[s] < dmax) { deg[s]++; total++; }
       if (i > (uint64_t)Q * 4096ULL) return -2;                       /* cannot reach the total */
     }

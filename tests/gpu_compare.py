@@ -1,0 +1,46 @@
+"""Element-by-element comparison of one GPU channel against one CPU-checker stream."""
+from __future__ import annotations
+
+import numpy as np
+
+
+def sorted_tokens(tok):
+    o = np.argsort(tok["state"], kind="stable")
+    return tok["state"][o], tok["cost"][o], tok["in_arc"][o]
+
+
+def compare_channel(dec, ch, od, frames=None, lattice=True, label=""):
+    """dec: WfstDecoder, ch: channel id, od: OracleDecoder fed the same rows.
+    frames: iterable of frame indices to compare (default: all).  Bit-exact everywhere."""
+    st = dec.stats(ch)
+    want_status = {0: 0, 1: -8, 2: -9}[od.status]
+    assert st["status"] == want_status, f"{label} status {st['status']} != {want_status}"
+    assert st["frames"] == od.num_frames, f"{label} frames {st['frames']} != {od.num_frames}"
+    assert st["arcs_expanded"] == od.arcs_expanded, f"{label} arcs_expanded {st['arcs_expanded']} != {od.arcs_expanded}"
+    assert st["max_tokens_pre_prune"] == od.max_tokens_pre_prune, label
+    assert st["max_tokens"] == od.max_tokens, label
+    if frames is None:
+        frames = range(od.num_frames)
+    for f in frames:
+        gs, gc, ga = sorted_tokens(dec.tokens(ch, f))
+        os_, oc, oa = od.tokens(f)
+        assert np.array_equal(gs, os_), f"{label} frame {f}: token states differ ({len(gs)} vs {len(os_)})"
+        assert np.array_equal(gc.view(np.uint32), oc.view(np.uint32)), f"{label} frame {f}: costs differ"
+        assert np.array_equal(ga, oa), f"{label} frame {f}: best incoming arcs differ"
+    if lattice:
+        lat = dec.lattice_arcs(ch)
+        o = np.lexsort((lat["arc"], lat["frame"]))
+        fr, ar, ex = od.lattice()
+        assert len(lat) == len(fr), f"{label} lattice size {len(lat)} != {len(fr)}"
+        assert np.array_equal(lat["frame"][o], fr) and np.array_equal(lat["arc"][o], ar), f"{label} lattice arcs differ"
+        assert np.array_equal(lat["extra_cost"][o].view(np.uint32), ex.view(np.uint32)), f"{label} extra costs differ"
+        assert st["lattice_arcs"] == len(fr)
+    if od.status == 0:
+        for use_final in (True, False):
+            bp = od.best_path(use_final)
+            g = dec.best_path(ch, use_final)
+            assert np.array_equal(g["words"], bp["words"]), f"{label} best-path words differ"
+            assert np.float32(g["total_cost"]).view(np.uint32) == np.float32(bp["total_cost"]).view(np.uint32), label
+            assert g["reached_final"] == bp["reached_final"], label
+            ga = dec.best_path_arcs(ch, use_final)
+            assert np.array_equal(ga["arcs"].astype(np.int64), bp["arcs"]), f"{label} best-path arcs differ"

@@ -1,0 +1,74 @@
+"""The C-ABI library loads (no GPU needed) and exports every function the header declares;
+host-side argument checks that need no device."""
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "wfst_decode.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(wfst_decode_\w+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1910_10032_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    return binding
+
+
+def test_header_and_binding_list_the_same_functions(B):
+    assert declared_functions() == sorted(B.EXPORTS)
+
+
+def test_library_exports_every_declared_function(B):
+    L = B.lib()
+    for name in declared_functions():
+        assert hasattr(L, name), name
+
+
+def test_strerror_and_null_arguments(B):
+    L = B.lib()
+    assert L.wfst_decode_strerror(0) == b"ok"
+    assert L.wfst_decode_strerror(B.WFST_E_DEAD_CHANNEL) == b"no token survived"
+    assert L.wfst_decode_graph_load(None, None) == B.WFST_E_INVALID_ARG
+    assert L.wfst_decode_create(None, None, None) == B.WFST_E_INVALID_ARG
+    assert L.wfst_decode_advance(None, None, 0, None, None, None, None) == B.WFST_E_INVALID_ARG
+    assert L.wfst_decode_graph_bytes(None, None, None) == B.WFST_E_INVALID_ARG
+
+
+def test_malformed_graphs_are_rejected_before_any_device_work(B):
+    import ctypes as C
+
+    import numpy as np
+    from helpers import graph_from_arcs
+    good = [(0, 1, 1, 0, 1.0), (1, 2, 0, 3, 0.5), (1, 0, 2, 0, 2.0)]
+
+    def load(g):
+        keep = [np.ascontiguousarray(g.row_offsets, np.int64), g.ilabel, g.olabel, g.weight, g.nextstate, g.final_cost]
+        csr = B.wfst_csr_t(g.num_states, g.num_arcs, g.start_state, g.num_pdfs, *[a.ctypes.data for a in keep])
+        h = C.c_void_p()
+        return B.lib().wfst_decode_graph_load(C.byref(csr), C.byref(h))
+
+    def variant(edit):
+        g = graph_from_arcs(3, good, 2, finals={2: 0.0})
+        edit(g)
+        return g
+
+    cases = [
+        lambda g: g.row_offsets.__setitem__(1, 4),            # offset beyond the next one and num_arcs
+        lambda g: g.nextstate.__setitem__(0, 3),              # destination out of range
+        lambda g: g.ilabel.__setitem__(0, 3),                 # pdf id beyond num_pdfs
+        lambda g: g.ilabel.__setitem__(0, -1),
+        lambda g: g.weight.__setitem__(0, np.nan),
+        lambda g: g.weight.__setitem__(1, -0.5),              # negative non-emitting weight
+        lambda g: g.final_cost.__setitem__(0, -np.inf),
+        lambda g: setattr(g, "start_state", 3),
+    ]
+    for edit in cases:
+        assert load(variant(edit)) == B.WFST_E_BAD_GRAPH

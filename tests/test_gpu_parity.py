@@ -1,0 +1,196 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU checker on the same
+seeded inputs — token sets, costs, best incoming arcs, lattice records, best paths and the
+canonical arc counts, all bit-exact."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from gpu_compare import compare_channel
+from helpers import random_graph
+
+pytestmark = pytest.mark.gpu
+F32 = np.float32
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1910_10032_amd import binding
+    binding.lib()          # fails loudly if the HIP library is not built
+    return binding
+
+
+def run_pair(torch, B, g, rows_per_stream, beam, lbeam, alpha, chunks=None, max_lanes=None, **kw):
+    """Decode streams on the GPU (one channel each, all lanes in one call per chunk) and on the checker."""
+    n = len(rows_per_stream)
+    T = max(len(r) for r in rows_per_stream)
+    gg = B.WfstGraph(g)
+    dec = B.WfstDecoder(gg, beam, lbeam, alpha, num_channels=n, max_lanes=max_lanes or n, max_frames=max(T, 1), **kw)
+    chans = list(range(n))
+    dec.init_channels(chans)
+    dev_rows = [torch.from_numpy(np.ascontiguousarray(r, F32)).cuda() if len(r) else
+                torch.empty((0, g.num_pdfs), dtype=torch.float32, device="cuda") for r in rows_per_stream]
+    chunks = chunks or [T]
+    pos = 0
+    for c in chunks:
+        lanes, tens = [], []
+        for i in chans:
+            seg = dev_rows[i][pos:pos + c]
+            if seg.shape[0] > 0:
+                lanes.append(i); tens.append(seg)
+        ml = max_lanes or n
+        for k in range(0, len(lanes), ml):
+            dec.advance(lanes[k:k + ml], tens[k:k + ml])
+        pos += c
+    torch.cuda.synchronize()
+    og = oracle.OracleGraph(g)
+    ods = []
+    for r in rows_per_stream:
+        od = oracle.OracleDecoder(og, beam, lbeam, alpha)
+        if len(r):
+            od.advance(np.ascontiguousarray(r, F32))
+        ods.append(od)
+    return dec, ods, gg
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_small_random_graphs(torch_cuda, B, seed):
+    rng = np.random.default_rng(1000 + seed)
+    integer = bool(seed % 2)
+    g = random_graph(rng, num_states=80, n_emit_per_state=(1, 5), eps_prob=0.03, num_pdfs=12, wmax=4,
+                     integer=integer, eps_first=bool(seed % 3 == 0), n_final=6)
+    rows = []
+    for s in range(5):
+        T = int(rng.integers(1, 40))
+        rows.append((-rng.integers(0, 5, size=(T, 12)).astype(F32)) if integer else rng.normal(-4, 2, size=(T, 12)).astype(F32))
+    rows.append(np.zeros((0, 12), F32))          # a stream that gets no frames
+    dec, ods, _ = run_pair(torch_cuda, B, g, rows, beam=7.0, lbeam=3.0, alpha=20)
+    for ch, od in enumerate(ods):
+        compare_channel(dec, ch, od, label=f"seed{seed}/ch{ch}")
+
+
+def test_max_active_ties(torch_cuda, B):
+    """Integer costs: the max-active cut falls inside large groups of equal cost."""
+    rng = np.random.default_rng(77)
+    g = random_graph(rng, num_states=400, n_emit_per_state=(3, 6), eps_prob=0.004, num_pdfs=6, wmax=2, integer=True, n_final=20)
+    rows = [-rng.integers(0, 3, size=(30, 6)).astype(F32) for _ in range(3)]
+    dec, ods, _ = run_pair(torch_cuda, B, g, rows, beam=6.0, lbeam=2.0, alpha=37, token_capacity=2048)
+    for ch, od in enumerate(ods):
+        assert od.max_tokens_pre_prune > 37
+        compare_channel(dec, ch, od, label=f"ties/ch{ch}")
+
+
+def test_config0_full(torch_cuda, B):
+    c = synth.configs()[0]
+    g = synth.make_graph(c.graph)
+    rows = [c.loglikes(0, 0, c.length(0))]
+    dec, ods, _ = run_pair(torch_cuda, B, g, rows, c.beam, c.lattice_beam, c.max_active, lattice_capacity=1 << 20)
+    compare_channel(dec, 0, ods[0], label="cfg0")
+
+
+def test_config0_chunked_interleaved_lanes(torch_cuda, B):
+    """Chunked calls, several channels, fewer lanes than channels: same results (Section 3.1)."""
+    c = synth.configs()[0]
+    g = synth.make_graph(c.graph)
+    rows = [c.loglikes(s, 0, 60 + 7 * s) for s in range(5)]
+    dec, ods, _ = run_pair(torch_cuda, B, g, rows, c.beam, c.lattice_beam, c.max_active, chunks=[13, 1, 50, 40],
+                           max_lanes=2, lattice_capacity=1 << 20)
+    for ch, od in enumerate(ods):
+        compare_channel(dec, ch, od, label=f"cfg0-chunk/ch{ch}")
+
+
+def test_config1_prefix(torch_cuda, B):
+    """Config 1 (200k states, max-active saturates): first 120 frames, every frame compared."""
+    c = synth.configs()[1]
+    g = synth.make_graph(c.graph)
+    rows = [c.loglikes(0, 0, 120)]
+    dec, ods, _ = run_pair(torch_cuda, B, g, rows, c.beam, c.lattice_beam, c.max_active, token_capacity=1 << 16,
+                           lattice_capacity=1 << 21)
+    assert ods[0].max_tokens_pre_prune > c.max_active
+    compare_channel(dec, 0, ods[0], label="cfg1")
+
+
+def test_dead_and_bad_scores(torch_cuda, B):
+    rng = np.random.default_rng(5)
+    g = random_graph(rng, num_states=30, n_emit_per_state=(1, 3), eps_prob=0.05, num_pdfs=5)
+    base = rng.normal(-3, 1, size=(8, 5)).astype(F32)
+    dead = base.copy(); dead[3, :] = -np.inf
+    nan = base.copy(); nan[2, :] = np.nan
+    pinf = base.copy(); pinf[5, :] = np.inf
+    dec, ods, _ = run_pair(torch_cuda, B, g, [base, dead, nan, pinf], beam=6.0, lbeam=3.0, alpha=15)
+    assert [od.status for od in ods] == [0, 1, 2, 2]
+    for ch, od in enumerate(ods):
+        compare_channel(dec, ch, od, label=f"err/ch{ch}")
+    with pytest.raises(B.WfstError) as e:
+        dec.best_path(1)
+    assert e.value.code == B.WFST_E_DEAD_CHANNEL
+    with pytest.raises(B.WfstError) as e:
+        dec.best_path(2)
+    assert e.value.code == B.WFST_E_NAN_INPUT
+
+
+def test_overflows_are_sticky_and_local(torch_cuda, B):
+    c = synth.configs()[0]
+    g = synth.make_graph(c.graph)
+    rows = [c.loglikes(0, 0, 30), c.loglikes(1, 0, 30)]
+    gg = B.WfstGraph(g)
+    # token capacity far too small for this workload: the channels must stop with an error
+    dec = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=2, max_lanes=2, max_frames=30, token_capacity=16)
+    dec.init_channels([0, 1])
+    t = [torch_cuda.from_numpy(r).cuda() for r in rows]
+    dec.advance([0, 1], t)
+    torch_cuda.cuda.synchronize()
+    assert dec.stats(0)["status"] == B.WFST_E_TOKEN_OVERFLOW
+    # a fresh decoder on the same graph still decodes correctly after the other one overflowed
+    dec2, ods, _ = run_pair(torch_cuda, B, g, rows, c.beam, c.lattice_beam, c.max_active, lattice_capacity=1 << 20)
+    compare_channel(dec2, 0, ods[0], label="after-overflow")
+    # lattice buffer too small
+    dec3 = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=1, max_lanes=1, max_frames=30, lattice_capacity=100)
+    dec3.init_channels([0])
+    dec3.advance([0], [t[0]])
+    torch_cuda.cuda.synchronize()
+    assert dec3.stats(0)["status"] == B.WFST_E_LATTICE_OVERFLOW
+
+
+def test_argument_errors(torch_cuda, B):
+    rng = np.random.default_rng(6)
+    g = random_graph(rng, num_states=10, n_emit_per_state=(1, 2), eps_prob=0.1, num_pdfs=3)
+    gg = B.WfstGraph(g)
+    dec = B.WfstDecoder(gg, 5.0, 2.0, 10, num_channels=3, max_lanes=2, max_frames=4)
+    t = torch_cuda.zeros((2, 3), dtype=torch_cuda.float32, device="cuda")
+    for bad, code in (([5], B.WFST_E_BAD_CHANNEL), ([1], B.WFST_E_NOT_INIT)):
+        with pytest.raises(B.WfstError) as e:
+            dec.advance(bad, [t] * len(bad))
+        assert e.value.code == code
+    dec.init_channels([0, 1, 2])
+    with pytest.raises(B.WfstError) as e:
+        dec.advance([0, 0], [t, t])
+    assert e.value.code == B.WFST_E_BAD_CHANNEL              # a channel twice in one call
+    with pytest.raises(B.WfstError) as e:
+        dec.advance([0, 1, 2], [t, t, t])
+    assert e.value.code == B.WFST_E_INVALID_ARG              # more lanes than max_lanes
+    dec.advance([0], [t]); dec.advance([0], [t])
+    with pytest.raises(B.WfstError) as e:
+        dec.advance([0], [t])
+    assert e.value.code == B.WFST_E_HISTORY_OVERFLOW         # max_frames exhausted
+    bad_g = random_graph(rng, num_states=10, n_emit_per_state=(1, 2), eps_prob=0.1, num_pdfs=3)
+    bad_g.nextstate[0] = 99
+    with pytest.raises(B.WfstError) as e:
+        B.WfstGraph(bad_g)
+    assert e.value.code == B.WFST_E_BAD_GRAPH
+
+
+def test_device_loglikes_match_host(torch_cuda):
+    c = synth.configs()[2]
+    out = torch_cuda.empty((37, c.graph.num_pdfs), dtype=torch_cuda.float32, device="cuda")
+    synth.device_loglikes(out, c.ll_seed, 5, 11, c.ll_mu, c.ll_sigma, c.ll_boost)
+    torch_cuda.cuda.synchronize()
+    host = synth.host_loglikes(c.ll_seed, 5, 11, 37, c.graph.num_pdfs, c.ll_mu, c.ll_sigma, c.ll_boost)
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), host.view(np.uint32))
