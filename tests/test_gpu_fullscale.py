@@ -1,0 +1,105 @@
+"""GPU parity at the full sizes of configs 2, 3 and 4, in the launch configuration the
+benchmark times (all channels of the config in every call): a sample of channels is
+compared with the CPU checker frame by frame — token sets, costs, best incoming arcs,
+lattice records, best paths, arc counts — bit-exact.  Streams are independent, so the
+checker can decode the sampled ones on their own."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from gpu_compare import sorted_tokens
+
+pytestmark = pytest.mark.gpu
+
+
+def decode_and_compare(cfg, sample, token_capacity, history_capacity, lattice_capacity, frame_step=1):
+    import torch
+
+    from paper_1910_10032_amd import binding as B
+    assert torch.cuda.is_available()
+    g = synth.make_graph(cfg.graph)
+    graph = B.WfstGraph(g)
+    n_ch, P = cfg.n_streams, cfg.graph.num_pdfs
+    lens = np.array([cfg.length(s) for s in range(n_ch)], np.int64)
+    T = int(lens.max())
+    dec = B.WfstDecoder(graph, cfg.beam, cfg.lattice_beam, cfg.max_active, num_channels=n_ch, max_lanes=n_ch,
+                        max_frames=T, token_capacity=token_capacity, history_capacity=history_capacity,
+                        lattice_capacity=lattice_capacity)
+    # scores of all streams, ragged, in one device buffer
+    starts = np.concatenate([[0], np.cumsum(lens)])
+    scores = torch.empty((int(starts[-1]), P), dtype=torch.float32, device="cuda")
+    for s in range(n_ch):
+        synth.device_loglikes(scores[starts[s]:starts[s + 1]], cfg.ll_seed, s, 0, cfg.ll_mu, cfg.ll_sigma, cfg.ll_boost)
+    torch.cuda.synchronize()
+    chans = np.arange(n_ch, dtype=np.int32)
+    dec.init_channels(chans)
+    chunk = cfg.chunk or T
+    stream = torch.cuda.current_stream().cuda_stream
+    lat = {s: [] for s in sample}
+    base = scores.data_ptr()
+    for f0 in range(0, T, chunk):
+        nfr = np.clip(lens - f0, 0, chunk).astype(np.int32)
+        ptrs = (base + (starts[:-1] + np.minimum(f0, lens)) * P * 4).astype(np.uint64)
+        dec.advance_ptrs(chans, ptrs, np.full(n_ch, P, np.int32), nfr, stream)
+        if cfg.chunk:                                  # online: every channel is drained after every chunk
+            recs, offs = dec.lattice_arcs_batch(chans)
+            for s in sample:
+                lat[s].append(recs[offs[s]:offs[s + 1]])
+    if not cfg.chunk:                                  # offline: one readout per sampled channel at the end
+        for s in sample:
+            lat[s].append(dec.lattice_arcs(s))
+    torch.cuda.synchronize()
+    statuses = [dec.stats(int(c))["status"] for c in chans]
+    assert all(st == 0 for st in statuses), f"channels with errors: {[(i, s) for i, s in enumerate(statuses) if s][:5]}"
+    og = oracle.OracleGraph(g)
+    for s in sample:
+        od = oracle.OracleDecoder(og, cfg.beam, cfg.lattice_beam, cfg.max_active)
+        od.advance(cfg.loglikes(s, 0, int(lens[s])))
+        st = dec.stats(s)
+        label = f"{cfg.name}/ch{s}"
+        assert st["frames"] == od.num_frames == lens[s] + 1, label
+        assert st["arcs_expanded"] == od.arcs_expanded, label
+        assert st["max_tokens_pre_prune"] == od.max_tokens_pre_prune and st["max_tokens"] == od.max_tokens, label
+        for f in list(range(0, od.num_frames, frame_step)) + [od.num_frames - 1]:
+            gs, gc, ga = sorted_tokens(dec.tokens(s, f))
+            os_, oc, oa = od.tokens(f)
+            assert np.array_equal(gs, os_), f"{label} frame {f}: states"
+            assert np.array_equal(gc.view(np.uint32), oc.view(np.uint32)), f"{label} frame {f}: costs"
+            assert np.array_equal(ga, oa), f"{label} frame {f}: arcs"
+        got = np.concatenate(lat[s])
+        o = np.lexsort((got["arc"], got["frame"]))
+        fr, ar, ex = od.lattice()
+        assert len(got) == len(fr) == st["lattice_arcs"], label
+        assert np.array_equal(got["frame"][o], fr) and np.array_equal(got["arc"][o], ar), label
+        assert np.array_equal(got["extra_cost"][o].view(np.uint32), ex.view(np.uint32)), label
+        for use_final in (True, False):
+            bp, gp = od.best_path(use_final), dec.best_path(s, use_final)
+            assert np.array_equal(gp["words"], bp["words"]), label
+            assert np.float32(gp["total_cost"]).view(np.uint32) == np.float32(bp["total_cost"]).view(np.uint32), label
+            assert gp["reached_final"] == bp["reached_final"], label
+            assert np.array_equal(dec.best_path_arcs(s, use_final)["arcs"].astype(np.int64), bp["arcs"]), label
+    # every channel, cheaply: the batch best path agrees with the single-channel call
+    batch = dec.best_path_batch(chans[:8], use_final=True)
+    for c, r in zip(chans[:8], batch):
+        one = dec.best_path(int(c), True)
+        assert r["status"] == 0 and np.array_equal(r["words"], one["words"]) and r["total_cost"] == one["total_cost"]
+    return dec
+
+
+def test_config3_online_500_channels():
+    cfg = synth.configs()[3]
+    decode_and_compare(cfg, sample=[0, 137, 499], token_capacity=16384, history_capacity=2_500_000,
+                       lattice_capacity=400_000)
+
+
+def test_config2_offline_ragged_batch():
+    cfg = synth.configs()[2]
+    decode_and_compare(cfg, sample=[0, 41, 99], token_capacity=32768, history_capacity=4_000_000,
+                       lattice_capacity=6_000_000)
+
+
+def test_config4_large_graph():
+    cfg = synth.configs()[4]
+    decode_and_compare(cfg, sample=[3, 150], token_capacity=60000, history_capacity=12_000_000,
+                       lattice_capacity=14_000_000, frame_step=3)
