@@ -42,7 +42,18 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-readout", action="store_true", help="time the advance calls only")
     ap.add_argument("--cpu-streams", type=int, default=12)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run only a plain 1 GiB device copy (calibrates the HBM byte counters under rocprofv3)")
     args = ap.parse_args()
+    if args.copy_probe:
+        import torch
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": src.numel() * 4, "copy_probe_bytes_written": src.numel() * 4, "copies": 4}))
+        return 0
     if args.gpus != 1:
         print("bench.py: this build decodes on one GPU only (streams are independent; more GPUs would each "
               "run their own decoder on a share of the channels) — run with --gpus 1", file=sys.stderr)

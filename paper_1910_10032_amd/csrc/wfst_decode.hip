@@ -264,6 +264,10 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
   if (!rc) rc = dev_alloc(d, &d->d_chans, std::max(nc, nl));
   if (!rc) rc = dev_alloc(d, &d->d_pathout, std::max(nc, nl));
   if (!rc) rc = dev_alloc(d, &d->d_cnt, 1);
+#ifdef WFST_PHASE_TIMING
+  if (!rc) rc = dev_alloc(d, &D.dbg, 8 + 8192);
+  if (!rc && hipMemset(D.dbg, 0, 8 * (8 + 8192)) != hipSuccess) rc = WFST_E_DEVICE;
+#endif
   if (!rc) rc = dev_alloc(d, &d->d_offs, std::max(nc, nl) + 1);
   if (!rc) {
     bool ok = hipMemset(D.chan, 0, sizeof(ChanState) * nc) == hipSuccess;
@@ -524,6 +528,16 @@ int wfst_decode_stats(wfst_decoder_t *d, int32_t channel, wfst_stats_t *out) {
   out->status = cs.status;
   return 0;
 }
+
+#ifdef WFST_PHASE_TIMING
+// Instrumented builds only: summed per-phase wall-clock ticks (100 MHz) of workgroup leaders.
+int wfst_debug_phase_times(wfst_decoder_t *d, unsigned long long *out8, int reset) {
+  HIP_TRY(hipDeviceSynchronize());
+  HIP_TRY(hipMemcpy(out8, d->dev.dbg, 8 * (8 + 8192), hipMemcpyDeviceToHost));
+  if (reset) HIP_TRY(hipMemset(d->dev.dbg, 0, 8 * (8 + 8192)));
+  return 0;
+}
+#endif
 
 int wfst_decode_set_profiling(wfst_decoder_t *d, int32_t on) {
   if (!d) return WFST_E_INVALID_ARG;

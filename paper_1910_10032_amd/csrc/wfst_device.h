@@ -37,10 +37,9 @@ struct GraphDev {
 struct __align__(16) Slot {
   unsigned long long val;    // min packed candidate; ~0 when empty
   uint32_t handle;           // EMPTY or the state handle
-  uint32_t aux;              // 0xFFFFFFFF fresh; bit 31 cleared once its epsilon arcs were
-                             // counted; after pruning: index in the new frame, or 0xFFFFFFFF
+  uint32_t aux;              // flag bits while the frame is built; after pruning: index of
+                             // the kept token in the new frame, or 0xFFFFFFFF
 };
-constexpr uint32_t AUX_GONE = 0x7FFFFFFFu;  // aux >= AUX_GONE: the token was not kept
 
 // queue entry: slot index | Q_EPS (state has epsilon arcs) | Q_DUP (re-expansion request)
 constexpr uint32_t Q_DUP = 0x80000000u;
@@ -93,6 +92,7 @@ struct DecDev {
   uint32_t H;
   int32_t hbits, qcap, auxcap, tokcap, max_frames, max_active, lattice_on;
   float beam, lattice_beam;
+  unsigned long long *dbg;   // phase timers of instrumented builds, else null
 };
 
 // error codes mirrored from the public header (device code cannot include it cleanly)

@@ -31,7 +31,7 @@
 namespace wfst {
 
 constexpr int NBINS = 2048;
-constexpr uint32_t F_NAN = 1, F_TOKOVF = 2, F_LATOVF = 4;
+constexpr uint32_t F_NAN = 1, F_TOKOVF = 2, F_LATOVF = 4, F_RESTART = 8;
 constexpr uint32_t KEY_NONE = 0xFFFFFFFFu;
 constexpr uint32_t KEY_PINF = 0xFF800000u;    // okey(+inf)
 
@@ -57,13 +57,19 @@ __device__ __forceinline__ uint32_t slot_hash(uint32_t handle, int hbits) {
   return (handle * 2654435761u) >> (32 - hbits);
 }
 
+// Table words are read through these: in global memory with loads that bypass the per-CU
+// vector cache (see ld32), in LDS with plain loads.
+template <bool LDS> __device__ __forceinline__ uint32_t tl32(const uint32_t *p) { return LDS ? *p : ld32(p); }
+template <bool LDS> __device__ __forceinline__ unsigned long long tl64(const unsigned long long *p) { return LDS ? *p : ld64(p); }
+
 // Offer candidate K for state `handle`.  Returns the slot, or -1 if the table is full.
+template <bool LDS>
 __device__ __forceinline__ int ht_insert(Slot *slots, uint32_t mask, int hbits, uint32_t handle,
                                          unsigned long long K, bool &claimed, bool &improved) {
   uint32_t h = slot_hash(handle, hbits);
   claimed = false; improved = false;
   for (uint32_t probe = 0; probe <= mask; ++probe) {
-    uint32_t k = ld32(&slots[h].handle);
+    uint32_t k = tl32<LDS>(&slots[h].handle);
     if (k == EMPTY) {
       k = atomicCAS(&slots[h].handle, EMPTY, handle);
       if (k == EMPTY) { claimed = true; k = handle; }
@@ -77,16 +83,26 @@ __device__ __forceinline__ int ht_insert(Slot *slots, uint32_t mask, int hbits, 
   }
   return -1;
 }
+template <bool LDS>
 __device__ __forceinline__ int ht_find(const Slot *slots, uint32_t mask, int hbits, uint32_t handle) {
   uint32_t h = slot_hash(handle, hbits);
   for (uint32_t probe = 0; probe <= mask; ++probe) {
-    uint32_t k = ld32(&slots[h].handle);
+    uint32_t k = tl32<LDS>(&slots[h].handle);
     if (k == handle) return (int)h;
     if (k == EMPTY) return -1;
     h = (h + 1) & mask;
   }
   return -1;
 }
+
+// Small frames keep the state table in LDS; a frame that outgrows it is redone with the
+// lane's table in global memory (nothing is committed before the contraction stage).
+constexpr int LDS_SLOTS = 4096, LDS_HBITS = 12, LDS_CLAIM_LIMIT = 3072, LDS_NIN_MAX = 1024;
+// Slot::aux while a frame is being built (afterwards: index of the kept token, or ~0):
+constexpr uint32_t A_FRESH = 0x80000000u;  // epsilon out-degree not counted yet
+constexpr uint32_t A_EPS = 0x40000000u;    // (LDS table) the state has epsilon arcs
+constexpr uint32_t A_DIRTY = 0x20000000u;  // (LDS table) must be (re)expanded by the closure
+constexpr uint32_t A_KEPT_MAX = 0x20000000u;  // aux < A_KEPT_MAX: index of the kept token
 
 template <int NT>
 struct LaneShared {
@@ -96,12 +112,22 @@ struct LaneShared {
   uint32_t base[NT];
   uint32_t hist[NBINS];
   uint32_t qtail, nclaim, auxn, best, flags, nvalid, nout, latn, kmin, kmax;
-  uint32_t sel_bin, sel_below, sel_cnt;
+  uint32_t sel_bin, sel_below, sel_cnt, any;
   unsigned long long emit_arcs, eps_arcs;
   // channel state, cached for the duration of the call
   int status, nf, max_pre, max_post, iters_max;
   long long hist_used, lat_count, lat_total, arcs_expanded;
+#ifdef WFST_PHASE_TIMING
+  unsigned long long ph[8], tlast;
+#endif
+  Slot table[LDS_SLOTS];
 };
+
+#ifdef WFST_PHASE_TIMING
+#define PHASE_MARK(k) do { if (threadIdx.x == 0) { unsigned long long t_ = wall_clock64(); S.ph[k] += t_ - S.tlast; S.tlast = t_; } } while (0)
+#else
+#define PHASE_MARK(k) do { } while (0)
+#endif
 
 template <int NT>
 __device__ __forceinline__ int block_excl_scan(int v, int *s_wave, int &total) {
@@ -168,18 +194,23 @@ __device__ void block_select(LaneShared<NT> &S, int n, uint32_t need, uint32_t l
   }
 }
 
-template <int NT>
-__device__ void lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &lp, const float *ll, bool is_init,
-                           Slot *slots, uint32_t *queue, Aux *aux, uint32_t *dkey, uint32_t *dslot,
+// One frame of one lane.  LDS: the state table lives in S.table (small frames), otherwise in
+// the lane's global table.  Returns false (LDS mode only) if the frame outgrew the LDS table
+// and must be redone with the global one; nothing has been committed in that case.
+template <int NT, bool LDS>
+__device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &lp, const float *ll, bool is_init,
+                           Slot *gslots, uint32_t *queue, Aux *aux, uint32_t *dkey, uint32_t *dslot,
                            long long *foff, HTok *hist, LatRec *lat) {
   const int tid = threadIdx.x;
   const uint32_t *rec = D.g.rec;
-  const uint32_t mask = D.H - 1;
-  const int hbits = D.hbits;
+  Slot *slots = LDS ? S.table : gslots;
+  const uint32_t mask = LDS ? (uint32_t)(LDS_SLOTS - 1) : D.H - 1;
+  const int hbits = LDS ? LDS_HBITS : D.hbits;
+  const Slot fresh{~0ull, EMPTY, A_FRESH};
 
   if (tid == 0) {
     S.qtail = 0; S.nclaim = 0; S.auxn = 0; S.best = KEY_NONE; S.flags = 0; S.nvalid = 0; S.nout = 0; S.latn = 0;
-    S.kmin = 0xFFFFFFFFu; S.kmax = 0; S.emit_arcs = 0; S.eps_arcs = 0;
+    S.kmin = 0xFFFFFFFFu; S.kmax = 0; S.emit_arcs = 0; S.eps_arcs = 0; S.any = 0;
   }
   __syncthreads();
   const int nf = S.nf;                       // index of the frame being written
@@ -187,15 +218,31 @@ __device__ void lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
   int abort_code = 0;
   if (nf > D.max_frames) abort_code = E_HISTORY_OVERFLOW;
 
+  // a claimed slot: count it, and remember it (queue entry / flags in the LDS slot)
+  auto on_claim = [&](int sl, uint32_t dw, bool dup) {
+    if (!dup) {
+      const uint32_t ci = atomicAdd(&S.nclaim, 1u);
+      if (ci >= (uint32_t)D.tokcap) atomicOr(&S.flags, F_TOKOVF);
+      else if (LDS && ci >= (uint32_t)LDS_CLAIM_LIMIT) atomicOr(&S.flags, F_RESTART);
+    }
+    if (LDS) {
+      if (dw & HAS_EPS) { atomicOr(&slots[sl].aux, A_EPS | A_DIRTY); S.any = 1; }
+    } else {
+      const uint32_t q = atomicAdd(&S.qtail, 1u);
+      if (q >= (uint32_t)D.qcap) atomicOr(&S.flags, F_TOKOVF);
+      else queue[q] = (uint32_t)sl | ((dw & HAS_EPS) ? Q_EPS : 0u) | (dup ? Q_DUP : 0u);
+    }
+  };
+
   // ---- 1. emitting expansion ------------------------------------------------------------
   if (abort_code == 0) {
     if (is_init) {
       if (tid == 0) {
         const uint32_t h = D.g.start_handle;
         bool cl, im;
-        int sl = ht_insert(slots, mask, hbits, h, pack(okey(0.0f), NO_ARC), cl, im);
-        queue[0] = (uint32_t)sl | (rec[3 * (size_t)h + 1] ? Q_EPS : 0u);
-        S.qtail = 1; S.nclaim = 1; S.best = okey(0.0f);
+        const int sl = ht_insert<LDS>(slots, mask, hbits, h, pack(okey(0.0f), NO_ARC), cl, im);
+        on_claim(sl, rec[3 * (size_t)h + 1] ? HAS_EPS : 0u, false);
+        S.best = okey(0.0f);
       }
     } else {
       const long long in_off = foff[nf - 1];
@@ -238,14 +285,10 @@ __device__ void lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
           const float cut = key2f(S.best) + D.beam;     // running bound, never below the final cutoff
           if (act && kx != KEY_NONE && x <= cut) {
             bool cl, im;
-            const int sl = ht_insert(slots, mask, hbits, dw & HMASK, pack(kx, r), cl, im);
-            if (sl < 0) atomicOr(&S.flags, F_TOKOVF);
+            const int sl = ht_insert<LDS>(slots, mask, hbits, dw & HMASK, pack(kx, r), cl, im);
+            if (sl < 0) atomicOr(&S.flags, LDS ? F_RESTART : F_TOKOVF);
             else {
-              if (cl) {
-                const uint32_t ci = atomicAdd(&S.nclaim, 1u), q = atomicAdd(&S.qtail, 1u);
-                if (ci >= (uint32_t)D.tokcap || q >= (uint32_t)D.qcap) atomicOr(&S.flags, F_TOKOVF);
-                else queue[q] = (uint32_t)sl | ((dw & HAS_EPS) ? Q_EPS : 0u);
-              }
+              if (cl) on_claim(sl, dw, false);
               if (D.lattice_on || im) {
                 const uint32_t ai = atomicAdd(&S.auxn, 1u);
                 if (ai >= (uint32_t)D.auxcap) atomicOr(&S.flags, F_LATOVF);
@@ -259,6 +302,7 @@ __device__ void lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
     }
   }
   __syncthreads();
+  PHASE_MARK(0);
   const uint32_t bestk = S.best;
   if (abort_code == 0) {
     const uint32_t fl = S.flags;
@@ -270,45 +314,81 @@ __device__ void lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
   const float cutoff = key2f(bestk) + D.beam;
 
   // ---- 2. non-emitting closure ----------------------------------------------------------
+  // expand the epsilon arcs of the token in slot `sp`, whose cost is within the cutoff
+  auto expand_eps = [&](Slot *sp, float c) {
+    const uint32_t h = tl32<LDS>(&sp->handle);
+    const uint32_t ne = rec[3 * (size_t)h], np = rec[3 * (size_t)h + 1];
+    if (atomicAnd(&sp->aux, ~A_FRESH) & A_FRESH) atomicAdd(&S.eps_arcs, (unsigned long long)np);
+    for (uint32_t k = 0; k < np; ++k) {
+      const uint32_t r = h + 1 + ne + k;
+      const uint32_t *a = rec + 3 * (size_t)r;
+      const uint32_t dw = a[0];
+      const float x = c + __uint_as_float(a[1]);
+      if (!(x <= cutoff)) continue;
+      bool cl, im;
+      const int sl = ht_insert<LDS>(slots, mask, hbits, dw & HMASK, pack(okey(x), r), cl, im);
+      if (sl < 0) { atomicOr(&S.flags, LDS ? F_RESTART : F_TOKOVF); continue; }
+      if (cl || im) on_claim(sl, dw, !cl);
+    }
+  };
   int iters = 0;
-  if (abort_code == 0) {
-    uint32_t w0 = 0, w1 = min(S.qtail, (uint32_t)D.qcap);
-    __syncthreads();
-    while (w0 < w1) {
-      for (uint32_t i = w0 + tid; i < w1; i += NT) {
-        const uint32_t e = queue[i];
-        if (!(e & Q_EPS)) continue;
-        Slot *sp = slots + (e & Q_SLOT);
-        const float c = key2f((uint32_t)(ld64(&sp->val) >> 32));
-        if (!(c <= cutoff)) continue;
-        const uint32_t h = ld32(&sp->handle);
-        const uint32_t ne = rec[3 * (size_t)h], np = rec[3 * (size_t)h + 1];
-        if (atomicAnd(&sp->aux, 0x7FFFFFFFu) >> 31) atomicAdd(&S.eps_arcs, (unsigned long long)np);
-        for (uint32_t k = 0; k < np; ++k) {
-          const uint32_t r = h + 1 + ne + k;
-          const uint32_t *a = rec + 3 * (size_t)r;
-          const uint32_t dw = a[0];
-          const float x = c + __uint_as_float(a[1]);
-          if (!(x <= cutoff)) continue;
-          bool cl, im;
-          const int sl = ht_insert(slots, mask, hbits, dw & HMASK, pack(okey(x), r), cl, im);
-          if (sl < 0) { atomicOr(&S.flags, F_TOKOVF); continue; }
-          if (cl || im) {
-            if (cl && atomicAdd(&S.nclaim, 1u) >= (uint32_t)D.tokcap) atomicOr(&S.flags, F_TOKOVF);
-            const uint32_t q = atomicAdd(&S.qtail, 1u);
-            if (q >= (uint32_t)D.qcap) atomicOr(&S.flags, F_TOKOVF);
-            else queue[q] = (uint32_t)sl | ((dw & HAS_EPS) ? Q_EPS : 0u) | (cl ? 0u : Q_DUP);
-          }
+  if (abort_code == 0 && !(LDS && (S.flags & F_RESTART))) {
+    if (LDS) {
+      while (S.any) {                                   // uniform: read between barriers
+        __syncthreads();
+        if (tid == 0) S.any = 0;
+        __syncthreads();
+        for (int i = tid; i < LDS_SLOTS; i += NT) {
+          Slot *sp = slots + i;
+          if (!(sp->aux & A_DIRTY)) continue;
+          atomicAnd(&sp->aux, ~A_DIRTY);                // before reading the cost: a later improvement re-marks it
+          const float c = key2f((uint32_t)(sp->val >> 32));
+          if (c <= cutoff) expand_eps(sp, c);
         }
+        ++iters;
+        __syncthreads();
       }
+    } else {
+      uint32_t w0 = 0, w1 = min(S.qtail, (uint32_t)D.qcap);
       __syncthreads();
-      w0 = w1; w1 = min(S.qtail, (uint32_t)D.qcap);
-      ++iters;
-      __syncthreads();
+      while (w0 < w1) {
+        for (uint32_t i = w0 + tid; i < w1; i += NT) {
+          const uint32_t e = queue[i];
+          if (!(e & Q_EPS)) continue;
+          Slot *sp = slots + (e & Q_SLOT);
+          const float c = key2f((uint32_t)(ld64(&sp->val) >> 32));
+          if (c <= cutoff) expand_eps(sp, c);
+        }
+        __syncthreads();
+        w0 = w1; w1 = min(S.qtail, (uint32_t)D.qcap);
+        ++iters;
+        __syncthreads();
+      }
     }
     if (S.flags & F_TOKOVF) abort_code = E_TOKEN_OVERFLOW;
   }
-  const uint32_t n_q = min(S.qtail, (uint32_t)D.qcap);
+  PHASE_MARK(1);
+  if (LDS) {
+    __syncthreads();
+    if (abort_code == 0 && (S.flags & F_RESTART)) {     // outgrew the LDS table: wipe it, redo with the global one
+      for (int i = tid; i < LDS_SLOTS; i += NT) slots[i] = fresh;
+      __syncthreads();
+      return false;
+    }
+  }
+  const uint32_t n_q = LDS ? (uint32_t)LDS_SLOTS : min(S.qtail, (uint32_t)D.qcap);
+  // token slots of this frame: all used LDS slots, or the non-duplicate queue entries
+  auto token_slot = [&](uint32_t i, uint32_t &sl, uint32_t &eps) -> bool {
+    if (LDS) {
+      if (slots[i].handle == EMPTY) return false;
+      sl = i; eps = slots[i].aux & A_EPS;
+      return true;
+    }
+    const uint32_t e = queue[i];
+    if (e & Q_DUP) return false;
+    sl = e & Q_SLOT; eps = e & Q_EPS;
+    return true;
+  };
 
   // ---- 3 + 4. max-active selection and contraction into the token history ---------------
   float cutoff_eff = cutoff;
@@ -319,27 +399,27 @@ __device__ void lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
     else if (nclaim <= (uint32_t)D.max_active) {
       // nothing can be pruned: every token within the beam is kept
       for (uint32_t i = tid; i < n_q; i += NT) {
-        const uint32_t e = queue[i];
-        if (e & Q_DUP) continue;
-        Slot *sp = slots + (e & Q_SLOT);
-        const unsigned long long v = ld64(&sp->val);
+        uint32_t sl, eps;
+        if (!token_slot(i, sl, eps)) continue;
+        Slot *sp = slots + sl;
+        const unsigned long long v = tl64<LDS>(&sp->val);
         const float c = key2f((uint32_t)(v >> 32));
         if (!(c <= cutoff)) continue;
         const uint32_t pos = atomicAdd(&S.nout, 1u);
         if (pos >= room) continue;
-        hist[out_base + pos] = HTok{ld32(&sp->handle) | ((e & Q_EPS) ? HAS_EPS : 0u), c, (uint32_t)v, NO_ARC};
+        hist[out_base + pos] = HTok{tl32<LDS>(&sp->handle) | (eps ? HAS_EPS : 0u), c, (uint32_t)v, NO_ARC};
         sp->aux = pos;
       }
       __syncthreads();
       if (tid == 0) S.nvalid = S.nout;
     } else {
       for (uint32_t i = tid; i < n_q; i += NT) {
-        const uint32_t e = queue[i];
-        if (e & Q_DUP) continue;
-        const uint32_t key = (uint32_t)(ld64(&slots[e & Q_SLOT].val) >> 32);
+        uint32_t sl, eps;
+        if (!token_slot(i, sl, eps)) continue;
+        const uint32_t key = (uint32_t)(tl64<LDS>(&slots[sl].val) >> 32);
         if (!(key2f(key) <= cutoff)) continue;
         const uint32_t p = atomicAdd(&S.nvalid, 1u);
-        dkey[p] = key; dslot[p] = e & (Q_SLOT | Q_EPS);
+        dkey[p] = key; dslot[p] = sl | (eps ? Q_EPS : 0u);
         atomicMin(&S.kmin, key); atomicMax(&S.kmax, key);
       }
       __syncthreads();
@@ -355,7 +435,7 @@ __device__ void lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
           block_select<NT>(S, n, need_eq, 0u, HMASK,
                            [&](int i, uint32_t &v) {
                              if (dkey[i] != theta) return false;
-                             v = ld32(&slots[dslot[i] & Q_SLOT].handle);
+                             v = tl32<LDS>(&slots[dslot[i] & Q_SLOT].handle);
                              return true;
                            }, h_theta, hl, he);
         }
@@ -364,12 +444,12 @@ __device__ void lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
       for (int i = tid; i < n; i += NT) {
         const uint32_t key = dkey[i], ds = dslot[i];
         Slot *sp = slots + (ds & Q_SLOT);
-        const uint32_t h = ld32(&sp->handle);
+        const uint32_t h = tl32<LDS>(&sp->handle);
         const bool keep = key < theta || (key == theta && h <= h_theta);
         uint32_t pos = 0xFFFFFFFFu;
         if (keep) pos = atomicAdd(&S.nout, 1u);
         if (pos < room) {
-          hist[out_base + pos] = HTok{h | ((ds & Q_EPS) ? HAS_EPS : 0u), key2f(key), (uint32_t)ld64(&sp->val), NO_ARC};
+          hist[out_base + pos] = HTok{h | ((ds & Q_EPS) ? HAS_EPS : 0u), key2f(key), (uint32_t)tl64<LDS>(&sp->val), NO_ARC};
           sp->aux = pos;
         } else {
           sp->aux = 0xFFFFFFFFu;
@@ -378,6 +458,7 @@ __device__ void lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
     }
   }
   __syncthreads();
+  PHASE_MARK(2);
   const uint32_t n_out = (abort_code == 0) ? min(S.nout, (uint32_t)D.max_active) : 0u;
 
   // ---- 5. lattice records and back-pointers ---------------------------------------------
@@ -392,9 +473,9 @@ __device__ void lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
     for (uint32_t i = tid; i < n_aux; i += NT) {
       const Aux a = aux[i];
       const Slot *sp = slots + a.slot;
-      const uint32_t pos = ld32(&sp->aux);
-      if (pos >= AUX_GONE) continue;
-      const unsigned long long v = ld64(&sp->val);
+      const uint32_t pos = tl32<LDS>(&sp->aux);
+      if (pos >= A_KEPT_MAX) continue;
+      const unsigned long long v = tl64<LDS>(&sp->val);
       if (pack(okey(a.x), a.arc) == v) hist[out_base + pos].prev = a.src;
       if (D.lattice_on && a.x <= cutoff_eff) {
         const float extra = a.x - key2f((uint32_t)(v >> 32));
@@ -411,12 +492,12 @@ __device__ void lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
         const uint32_t *a = rec + 3 * (size_t)r;
         const float x = t.cost + __uint_as_float(a[1]);
         if (!(x <= cutoff_eff)) continue;
-        const int sl = ht_find(slots, mask, hbits, a[0] & HMASK);
+        const int sl = ht_find<LDS>(slots, mask, hbits, a[0] & HMASK);
         if (sl < 0) continue;
         const Slot *sp = slots + sl;
-        const uint32_t pos = ld32(&sp->aux);
-        if (pos >= AUX_GONE) continue;
-        const unsigned long long v = ld64(&sp->val);
+        const uint32_t pos = tl32<LDS>(&sp->aux);
+        if (pos >= A_KEPT_MAX) continue;
+        const unsigned long long v = tl64<LDS>(&sp->val);
         if (pack(okey(x), r) == v) hist[out_base + pos].prev = j | PREV_SAME;
         if (D.lattice_on) {
           const float extra = x - key2f((uint32_t)(v >> 32));
@@ -426,10 +507,12 @@ __device__ void lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
     }
   }
   __syncthreads();
+  PHASE_MARK(3);
 
   // ---- 6. clear the table ---------------------------------------------------------------
-  const Slot fresh{~0ull, EMPTY, 0xFFFFFFFFu};
-  if (S.flags & F_TOKOVF) {
+  if (LDS) {
+    for (int i = tid; i < LDS_SLOTS; i += NT) slots[i] = fresh;
+  } else if (S.flags & F_TOKOVF) {
     for (uint32_t i = tid; i < D.H; i += NT) slots[i] = fresh;      // untracked claims: wipe everything
   } else {
     for (uint32_t i = tid; i < n_q; i += NT) {
@@ -450,9 +533,14 @@ __device__ void lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
     S.max_pre = max(S.max_pre, (int)S.nvalid);
     S.max_post = max(S.max_post, (int)n_out);
     S.iters_max = max(S.iters_max, iters);
+#ifdef WFST_PHASE_TIMING
+    S.ph[7] += iters;
+#endif
     if (abort_code != 0) S.status = abort_code;
   }
   __syncthreads();
+  PHASE_MARK(4);
+  return true;
 }
 
 // One workgroup per lane.  is_init: (re)start the lane's channel and write frame 0.
@@ -471,6 +559,8 @@ __global__ void __launch_bounds__(NT) k_advance(DecDev D, const LaneParam *__res
   HTok *hist = D.hist + (size_t)lp.chan * (size_t)D.hist_cap;
   LatRec *lat = D.lat + (size_t)lp.chan * (size_t)D.lat_cap;
 
+  const Slot fresh{~0ull, EMPTY, A_FRESH};
+  for (int i = tid; i < LDS_SLOTS; i += NT) S.table[i] = fresh;
   if (tid == 0) {
     if (is_init) {
       S.status = 0; S.nf = 0; S.hist_used = 0; S.lat_count = 0; S.lat_total = 0; S.arcs_expanded = 0;
@@ -481,24 +571,50 @@ __global__ void __launch_bounds__(NT) k_advance(DecDev D, const LaneParam *__res
       S.lat_total = cs->lat_total; S.arcs_expanded = cs->arcs_expanded; S.max_pre = cs->max_pre;
       S.max_post = cs->max_post; S.iters_max = cs->closure_iters_max;
     }
+#ifdef WFST_PHASE_TIMING
+    for (int k = 0; k < 8; ++k) S.ph[k] = 0;
+    S.tlast = wall_clock64();
+#endif
   }
   __syncthreads();
   const int nframes = is_init ? 1 : lp.n_frames;
   for (int f = 0; f < nframes; ++f) {
     if (S.status != 0) break;
-    lane_frame<NT>(D, S, lp, is_init ? nullptr : lp.ll + (size_t)f * (size_t)lp.stride, is_init != 0,
-                   slots, queue, aux, dkey, dslot, foff, hist, lat);
+    const float *ll = is_init ? nullptr : lp.ll + (size_t)f * (size_t)lp.stride;
+    const int nf = S.nf;
+    bool small = is_init != 0;
+    if (!small && nf >= 1 && nf <= D.max_frames) small = (foff[nf] - foff[nf - 1]) <= (long long)LDS_NIN_MAX;
+    bool done = false;
+    if (small) done = lane_frame<NT, true>(D, S, lp, ll, is_init != 0, slots, queue, aux, dkey, dslot, foff, hist, lat);
+    if (!done) {
+#ifdef WFST_PHASE_TIMING
+      if (tid == 0 && small) S.ph[6] += 1;
+#endif
+      lane_frame<NT, false>(D, S, lp, ll, is_init != 0, slots, queue, aux, dkey, dslot, foff, hist, lat);
+    }
+#ifdef WFST_PHASE_TIMING
+    if (tid == 0) S.ph[5] += 1;
+#endif
   }
   __syncthreads();
   if (tid == 0) {
     cs->status = S.status; cs->num_frames = S.nf; cs->hist_used = S.hist_used; cs->lat_count = S.lat_count;
     cs->lat_total = S.lat_total; cs->arcs_expanded = S.arcs_expanded; cs->max_pre = S.max_pre;
     cs->max_post = S.max_post; cs->closure_iters_max = S.iters_max;
+#ifdef WFST_PHASE_TIMING
+    if (D.dbg) {
+      for (int k = 0; k < 8; ++k) atomicAdd(D.dbg + k, S.ph[k]);
+      unsigned long long tot = 0;
+      for (int k = 0; k < 5; ++k) tot += S.ph[k];
+      D.dbg[8 + blockIdx.x] = tot;                      // this lane's time for the call
+      D.dbg[8 + 4096 + blockIdx.x] = (unsigned long long)(S.hist_used);
+    }
+#endif
   }
 }
 
 __global__ void k_fill_slots(Slot *slots, size_t n) {
-  const Slot fresh{~0ull, EMPTY, 0xFFFFFFFFu};
+  const Slot fresh{~0ull, EMPTY, A_FRESH};
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) slots[i] = fresh;
 }
 
