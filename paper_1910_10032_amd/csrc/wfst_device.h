@@ -46,7 +46,10 @@ constexpr uint32_t Q_DUP = 0x80000000u;
 constexpr uint32_t Q_EPS = 0x40000000u;
 constexpr uint32_t Q_SLOT = 0x3FFFFFFFu;
 
-struct __align__(16) Aux {   // an emitting candidate that entered the table
+// A candidate arc noted for the lattice stage.  Emitting: {slot of the destination, cost x,
+// arc, index of the source token in the previous frame}.  Epsilon (slot has bit 31 set):
+// {slot of the source, arc weight, arc, handle of the destination}.
+struct __align__(16) Aux {
   uint32_t slot; float x; uint32_t arc; uint32_t src;
 };
 

@@ -30,7 +30,7 @@
 
 namespace wfst {
 
-constexpr int NBINS = 2048;
+constexpr int NBINS = 1024;
 constexpr uint32_t F_NAN = 1, F_TOKOVF = 2, F_LATOVF = 4, F_RESTART = 8;
 constexpr uint32_t KEY_NONE = 0xFFFFFFFFu;
 constexpr uint32_t KEY_PINF = 0xFF800000u;    // okey(+inf)
@@ -98,36 +98,54 @@ __device__ __forceinline__ int ht_find(const Slot *slots, uint32_t mask, int hbi
 // Small frames keep the state table in LDS; a frame that outgrows it is redone with the
 // lane's table in global memory (nothing is committed before the contraction stage).
 constexpr int LDS_SLOTS = 4096, LDS_HBITS = 12, LDS_CLAIM_LIMIT = 3072, LDS_NIN_MAX = 1024;
+constexpr int EXP_U = 4;                   // arcs per thread and round of the emitting expansion
+constexpr int LAT_U = 4;                   // candidate records per thread and round of the lattice stage
+constexpr uint32_t AUX_EPS = 0x80000000u;  // Aux::slot flag: the record is an epsilon arc
+constexpr int LDS_QCAP = 4096;             // entries of the LDS token queue (16-bit each)
 // Slot::aux while a frame is being built (afterwards: index of the kept token, or ~0):
 constexpr uint32_t A_FRESH = 0x80000000u;  // epsilon out-degree not counted yet
-constexpr uint32_t A_EPS = 0x40000000u;    // (LDS table) the state has epsilon arcs
-constexpr uint32_t A_DIRTY = 0x20000000u;  // (LDS table) must be (re)expanded by the closure
 constexpr uint32_t A_KEPT_MAX = 0x20000000u;  // aux < A_KEPT_MAX: index of the kept token
+// LDS queue entry: slot (12 bits) | LQ_EPS | LQ_DUP
+constexpr uint32_t LQ_EPS = 0x4000u, LQ_DUP = 0x8000u, LQ_SLOT = 0x0FFFu;
 
 template <int NT>
 struct LaneShared {
   int wave_tmp[NT / 64];
-  int scan[NT];
-  float cost[NT];
-  uint32_t base[NT];
-  uint32_t hist[NBINS];
+  union {                      // the expansion's tile arrays and the selection's histogram never coexist
+    struct { int scan[NT]; float cost[NT]; uint32_t base[NT]; };
+    uint32_t hist[NBINS];
+  };
   uint32_t qtail, nclaim, auxn, best, flags, nvalid, nout, latn, kmin, kmax;
-  uint32_t sel_bin, sel_below, sel_cnt, any;
+  uint32_t sel_bin, sel_below, sel_cnt;
   unsigned long long emit_arcs, eps_arcs;
   // channel state, cached for the duration of the call
   int status, nf, max_pre, max_post, iters_max;
   long long hist_used, lat_count, lat_total, arcs_expanded;
 #ifdef WFST_PHASE_TIMING
-  unsigned long long ph[8], tlast;
+  unsigned long long ph[16], tlast, dbg_tok, dbg_iters, dbg_arcs;
 #endif
-  Slot table[LDS_SLOTS];
+  uint16_t lq[LDS_QCAP];       // token queue of small frames
+  Slot table[LDS_SLOTS];       // state table of small frames
 };
+static_assert(NBINS * 4 <= 512 * 12, "histogram must fit in the tile arrays");
 
 #ifdef WFST_PHASE_TIMING
 #define PHASE_MARK(k) do { if (threadIdx.x == 0) { unsigned long long t_ = wall_clock64(); S.ph[k] += t_ - S.tlast; S.tlast = t_; } } while (0)
 #else
 #define PHASE_MARK(k) do { } while (0)
 #endif
+
+// One counter update per wavefront: the lanes that call this together (same call site,
+// any subset of the wave) get consecutive indices from a single atomic add.
+__device__ __forceinline__ uint32_t wave_alloc(uint32_t *counter) {
+  const unsigned long long m = __ballot(1);
+  const int lane = threadIdx.x & 63;
+  const int leader = __ffsll((long long)m) - 1;
+  uint32_t base = 0;
+  if (lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(m));
+  base = (uint32_t)__shfl((int)base, leader, 64);
+  return base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+}
 
 template <int NT>
 __device__ __forceinline__ int block_excl_scan(int v, int *s_wave, int &total) {
@@ -210,7 +228,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
 
   if (tid == 0) {
     S.qtail = 0; S.nclaim = 0; S.auxn = 0; S.best = KEY_NONE; S.flags = 0; S.nvalid = 0; S.nout = 0; S.latn = 0;
-    S.kmin = 0xFFFFFFFFu; S.kmax = 0; S.emit_arcs = 0; S.eps_arcs = 0; S.any = 0;
+    S.kmin = 0xFFFFFFFFu; S.kmax = 0; S.emit_arcs = 0; S.eps_arcs = 0;
   }
   __syncthreads();
   const int nf = S.nf;                       // index of the frame being written
@@ -218,20 +236,22 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
   int abort_code = 0;
   if (nf > D.max_frames) abort_code = E_HISTORY_OVERFLOW;
 
-  // a claimed slot: count it, and remember it (queue entry / flags in the LDS slot)
+  // the frame's token queue: claimed slots, plus re-expansion requests for improved ones
+  const uint32_t qcap = LDS ? (uint32_t)LDS_QCAP : (uint32_t)D.qcap;
+  auto qget = [&](uint32_t i, uint32_t &sl, bool &eps, bool &dup) {
+    if (LDS) { const uint32_t e = S.lq[i]; sl = e & LQ_SLOT; eps = e & LQ_EPS; dup = e & LQ_DUP; }
+    else { const uint32_t e = queue[i]; sl = e & Q_SLOT; eps = e & Q_EPS; dup = e & Q_DUP; }
+  };
   auto on_claim = [&](int sl, uint32_t dw, bool dup) {
     if (!dup) {
-      const uint32_t ci = atomicAdd(&S.nclaim, 1u);
+      const uint32_t ci = wave_alloc(&S.nclaim);
       if (ci >= (uint32_t)D.tokcap) atomicOr(&S.flags, F_TOKOVF);
       else if (LDS && ci >= (uint32_t)LDS_CLAIM_LIMIT) atomicOr(&S.flags, F_RESTART);
     }
-    if (LDS) {
-      if (dw & HAS_EPS) { atomicOr(&slots[sl].aux, A_EPS | A_DIRTY); S.any = 1; }
-    } else {
-      const uint32_t q = atomicAdd(&S.qtail, 1u);
-      if (q >= (uint32_t)D.qcap) atomicOr(&S.flags, F_TOKOVF);
-      else queue[q] = (uint32_t)sl | ((dw & HAS_EPS) ? Q_EPS : 0u) | (dup ? Q_DUP : 0u);
-    }
+    const uint32_t q = wave_alloc(&S.qtail);
+    if (q >= qcap) atomicOr(&S.flags, LDS ? F_RESTART : F_TOKOVF);
+    else if (LDS) S.lq[q] = (uint16_t)((uint32_t)sl | ((dw & HAS_EPS) ? LQ_EPS : 0u) | (dup ? LQ_DUP : 0u));
+    else queue[q] = (uint32_t)sl | ((dw & HAS_EPS) ? Q_EPS : 0u) | (dup ? Q_DUP : 0u);
   };
 
   // ---- 1. emitting expansion ------------------------------------------------------------
@@ -247,58 +267,82 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
     } else {
       const long long in_off = foff[nf - 1];
       const int n_in = (int)(foff[nf] - in_off);
-      for (int tb = 0; tb < n_in; tb += NT) {
-        const int i = tb + tid;
-        int ne = 0; uint32_t h = 0; float c = 0.f;
+      // touch this frame's row of scores (one 64-byte line per thread) while the tokens'
+      // graph records are being fetched, so that the gathers by pdf id below hit L2
+      float touch = 0.f;
+      for (int p = tid * 16; p < D.g.num_pdfs; p += NT * 16) touch += ll[p];
+      // this thread's token of a tile: state handle, cost, emitting out-degree
+      auto load_token = [&](int i, uint32_t &h, float &c, int &ne) {
+        ne = 0; h = 0; c = 0.f;
         if (i < n_in) {
           const HTok t = hist[in_off + i];
           h = t.handle & HMASK; c = t.cost;
           ne = (int)rec[3 * (size_t)h];
         }
+      };
+      uint32_t h, hn = 0; float c, cn = 0.f; int ne, nen = 0;
+      load_token(tid, h, c, ne);
+      for (int tb = 0; tb < n_in; tb += NT) {
         int total;
         const int ex = block_excl_scan<NT>(ne, S.wave_tmp, total);
         S.scan[tid] = ex; S.cost[tid] = c; S.base[tid] = h + 1;
         __syncthreads();
+        PHASE_MARK(8);
         if (tid == 0) S.emit_arcs += (unsigned long long)total;
-        for (int j0 = 0; j0 < total; j0 += NT) {
-          const int j = j0 + tid;
-          const bool act = j < total;
-          float x = 0.f; uint32_t r = 0, dw = 0, kx = KEY_NONE; int k = 0;
-          if (act) {
-            int lo = 0, hi = NT - 1;             // largest k with scan[k] <= j
-            while (lo < hi) { int mid = (lo + hi + 1) >> 1; if (S.scan[mid] <= j) lo = mid; else hi = mid - 1; }
-            k = lo;
-            r = S.base[k] + (uint32_t)(j - S.scan[k]);
-            const uint32_t *a = rec + 3 * (size_t)r;
-            dw = a[0];
-            const float w = __uint_as_float(a[1]);
-            const float llv = ll[a[2]];
-            const float cw = S.cost[k] + w;
-            x = cw - llv;
-            if (x != x || x == -INFINITY) atomicOr(&S.flags, F_NAN); else kx = okey(x);
+        if (tb + NT < n_in) load_token(tb + NT + tid, hn, cn, nen);   // next tile, in flight during this one's rounds
+        // one thread per arc (Section 3.3), EXP_U arcs of the tile per thread and round so
+        // that their loads are in flight together
+        for (int j0 = 0; j0 < total; j0 += NT * EXP_U) {
+          float x[EXP_U], cw[EXP_U]; uint32_t r[EXP_U], dw[EXP_U], kx[EXP_U], pdf[EXP_U]; int kk[EXP_U];
+#pragma unroll
+          for (int u = 0; u < EXP_U; ++u) {
+            const int j = j0 + u * NT + tid;
+            kx[u] = KEY_NONE; kk[u] = -1; r[u] = 0; dw[u] = 0; pdf[u] = 0; cw[u] = 0.f; x[u] = 0.f;
+            if (j < total) {
+              int lo = 0, hi = NT - 1;             // largest k with scan[k] <= j
+              while (lo < hi) { int mid = (lo + hi + 1) >> 1; if (S.scan[mid] <= j) lo = mid; else hi = mid - 1; }
+              kk[u] = lo;
+              r[u] = S.base[lo] + (uint32_t)(j - S.scan[lo]);
+              const uint32_t *a = rec + 3 * (size_t)r[u];
+              dw[u] = a[0];
+              cw[u] = S.cost[lo] + __uint_as_float(a[1]);
+              pdf[u] = a[2];
+            }
           }
-          uint32_t m = kx;
+          uint32_t m = KEY_NONE;
+#pragma unroll
+          for (int u = 0; u < EXP_U; ++u) {
+            if (kk[u] >= 0) {
+              x[u] = cw[u] - ll[pdf[u]];
+              if (x[u] != x[u] || x[u] == -INFINITY) atomicOr(&S.flags, F_NAN); else kx[u] = okey(x[u]);
+              m = min(m, kx[u]);
+            }
+          }
 #pragma unroll
           for (int d = 32; d; d >>= 1) m = min(m, (uint32_t)__shfl_xor((int)m, d, 64));
           if ((tid & 63) == 0 && m != KEY_NONE) atomicMin(&S.best, m);
           __syncthreads();
+          PHASE_MARK(9);
           const float cut = key2f(S.best) + D.beam;     // running bound, never below the final cutoff
-          if (act && kx != KEY_NONE && x <= cut) {
+#pragma unroll
+          for (int u = 0; u < EXP_U; ++u) {
+            if (kx[u] == KEY_NONE || !(x[u] <= cut)) continue;
             bool cl, im;
-            const int sl = ht_insert<LDS>(slots, mask, hbits, dw & HMASK, pack(kx, r), cl, im);
-            if (sl < 0) atomicOr(&S.flags, LDS ? F_RESTART : F_TOKOVF);
-            else {
-              if (cl) on_claim(sl, dw, false);
-              if (D.lattice_on || im) {
-                const uint32_t ai = atomicAdd(&S.auxn, 1u);
-                if (ai >= (uint32_t)D.auxcap) atomicOr(&S.flags, F_LATOVF);
-                else aux[ai] = Aux{(uint32_t)sl, x, r, (uint32_t)(tb + k)};
-              }
+            const int sl = ht_insert<LDS>(slots, mask, hbits, dw[u] & HMASK, pack(kx[u], r[u]), cl, im);
+            if (sl < 0) { atomicOr(&S.flags, LDS ? F_RESTART : F_TOKOVF); continue; }
+            if (cl) on_claim(sl, dw[u], false);
+            if (D.lattice_on || im) {
+              const uint32_t ai = wave_alloc(&S.auxn);
+              if (ai >= (uint32_t)D.auxcap) atomicOr(&S.flags, F_LATOVF);
+              else aux[ai] = Aux{(uint32_t)sl, x[u], r[u], (uint32_t)(tb + kk[u])};
             }
           }
         }
         __syncthreads();
+        PHASE_MARK(10);
+        h = hn; c = cn; ne = nen;
       }
+      asm volatile("" ::"v"(touch));
     }
   }
   __syncthreads();
@@ -315,15 +359,27 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
 
   // ---- 2. non-emitting closure ----------------------------------------------------------
   // expand the epsilon arcs of the token in slot `sp`, whose cost is within the cutoff
-  auto expand_eps = [&](Slot *sp, float c) {
+  auto expand_eps = [&](uint32_t src_slot, float c) {
+    Slot *sp = slots + src_slot;
     const uint32_t h = tl32<LDS>(&sp->handle);
     const uint32_t ne = rec[3 * (size_t)h], np = rec[3 * (size_t)h + 1];
-    if (atomicAnd(&sp->aux, ~A_FRESH) & A_FRESH) atomicAdd(&S.eps_arcs, (unsigned long long)np);
+    // first expansion of this token: count its arcs and note every one of them (source slot,
+    // weight, arc, destination) so that the lattice stage can re-derive the candidates from
+    // final costs without reading the graph again
+    const bool first = atomicAnd(&sp->aux, ~A_FRESH) & A_FRESH;
+    uint32_t ai = 0;
+    if (first) {
+      atomicAdd(&S.eps_arcs, (unsigned long long)np);
+      ai = atomicAdd(&S.auxn, np);
+      if (ai + np > (uint32_t)D.auxcap) atomicOr(&S.flags, F_LATOVF);
+    }
     for (uint32_t k = 0; k < np; ++k) {
       const uint32_t r = h + 1 + ne + k;
       const uint32_t *a = rec + 3 * (size_t)r;
       const uint32_t dw = a[0];
-      const float x = c + __uint_as_float(a[1]);
+      const float w = __uint_as_float(a[1]);
+      if (first && ai + k < (uint32_t)D.auxcap) aux[ai + k] = Aux{src_slot | AUX_EPS, w, r, dw & HMASK};
+      const float x = c + w;
       if (!(x <= cutoff)) continue;
       bool cl, im;
       const int sl = ht_insert<LDS>(slots, mask, hbits, dw & HMASK, pack(okey(x), r), cl, im);
@@ -333,39 +389,24 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
   };
   int iters = 0;
   if (abort_code == 0 && !(LDS && (S.flags & F_RESTART))) {
-    if (LDS) {
-      while (S.any) {                                   // uniform: read between barriers
-        __syncthreads();
-        if (tid == 0) S.any = 0;
-        __syncthreads();
-        for (int i = tid; i < LDS_SLOTS; i += NT) {
-          Slot *sp = slots + i;
-          if (!(sp->aux & A_DIRTY)) continue;
-          atomicAnd(&sp->aux, ~A_DIRTY);                // before reading the cost: a later improvement re-marks it
-          const float c = key2f((uint32_t)(sp->val >> 32));
-          if (c <= cutoff) expand_eps(sp, c);
-        }
-        ++iters;
-        __syncthreads();
+    uint32_t w0 = 0, w1 = min(S.qtail, qcap);
+    __syncthreads();
+    while (w0 < w1) {
+      for (uint32_t i = w0 + tid; i < w1; i += NT) {
+        uint32_t sl; bool eps, dup;
+        qget(i, sl, eps, dup);
+        if (!eps) continue;
+        const float c = key2f((uint32_t)(tl64<LDS>(&slots[sl].val) >> 32));
+        if (c <= cutoff) expand_eps(sl, c);
       }
-    } else {
-      uint32_t w0 = 0, w1 = min(S.qtail, (uint32_t)D.qcap);
       __syncthreads();
-      while (w0 < w1) {
-        for (uint32_t i = w0 + tid; i < w1; i += NT) {
-          const uint32_t e = queue[i];
-          if (!(e & Q_EPS)) continue;
-          Slot *sp = slots + (e & Q_SLOT);
-          const float c = key2f((uint32_t)(ld64(&sp->val) >> 32));
-          if (c <= cutoff) expand_eps(sp, c);
-        }
-        __syncthreads();
-        w0 = w1; w1 = min(S.qtail, (uint32_t)D.qcap);
-        ++iters;
-        __syncthreads();
-      }
+      PHASE_MARK(11);
+      w0 = w1; w1 = min(S.qtail, qcap);
+      ++iters;
+      __syncthreads();
     }
     if (S.flags & F_TOKOVF) abort_code = E_TOKEN_OVERFLOW;
+    else if (S.flags & F_LATOVF) abort_code = E_LATTICE_OVERFLOW;
   }
   PHASE_MARK(1);
   if (LDS) {
@@ -376,18 +417,12 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
       return false;
     }
   }
-  const uint32_t n_q = LDS ? (uint32_t)LDS_SLOTS : min(S.qtail, (uint32_t)D.qcap);
-  // token slots of this frame: all used LDS slots, or the non-duplicate queue entries
+  const uint32_t n_q = min(S.qtail, qcap);
   auto token_slot = [&](uint32_t i, uint32_t &sl, uint32_t &eps) -> bool {
-    if (LDS) {
-      if (slots[i].handle == EMPTY) return false;
-      sl = i; eps = slots[i].aux & A_EPS;
-      return true;
-    }
-    const uint32_t e = queue[i];
-    if (e & Q_DUP) return false;
-    sl = e & Q_SLOT; eps = e & Q_EPS;
-    return true;
+    bool e, dup;
+    qget(i, sl, e, dup);
+    eps = e;
+    return !dup;
   };
 
   // ---- 3 + 4. max-active selection and contraction into the token history ---------------
@@ -405,7 +440,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
         const unsigned long long v = tl64<LDS>(&sp->val);
         const float c = key2f((uint32_t)(v >> 32));
         if (!(c <= cutoff)) continue;
-        const uint32_t pos = atomicAdd(&S.nout, 1u);
+        const uint32_t pos = wave_alloc(&S.nout);
         if (pos >= room) continue;
         hist[out_base + pos] = HTok{tl32<LDS>(&sp->handle) | (eps ? HAS_EPS : 0u), c, (uint32_t)v, NO_ARC};
         sp->aux = pos;
@@ -418,7 +453,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
         if (!token_slot(i, sl, eps)) continue;
         const uint32_t key = (uint32_t)(tl64<LDS>(&slots[sl].val) >> 32);
         if (!(key2f(key) <= cutoff)) continue;
-        const uint32_t p = atomicAdd(&S.nvalid, 1u);
+        const uint32_t p = wave_alloc(&S.nvalid);
         dkey[p] = key; dslot[p] = sl | (eps ? Q_EPS : 0u);
         atomicMin(&S.kmin, key); atomicMax(&S.kmax, key);
       }
@@ -447,7 +482,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
         const uint32_t h = tl32<LDS>(&sp->handle);
         const bool keep = key < theta || (key == theta && h <= h_theta);
         uint32_t pos = 0xFFFFFFFFu;
-        if (keep) pos = atomicAdd(&S.nout, 1u);
+        if (keep) pos = wave_alloc(&S.nout);
         if (pos < room) {
           hist[out_base + pos] = HTok{h | ((ds & Q_EPS) ? HAS_EPS : 0u), key2f(key), (uint32_t)tl64<LDS>(&sp->val), NO_ARC};
           sp->aux = pos;
@@ -466,42 +501,49 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
     const long long lat_base = S.lat_count;
     const uint32_t n_aux = min(S.auxn, (uint32_t)D.auxcap);
     auto emit_lat = [&](uint32_t arc, float extra) {
-      const uint32_t p = atomicAdd(&S.latn, 1u);
+      const uint32_t p = wave_alloc(&S.latn);
       if (lat_base + (long long)p >= D.lat_cap) atomicOr(&S.flags, F_LATOVF);
       else lat[lat_base + p] = LatRec{nf, arc, extra};
     };
-    for (uint32_t i = tid; i < n_aux; i += NT) {
-      const Aux a = aux[i];
-      const Slot *sp = slots + a.slot;
-      const uint32_t pos = tl32<LDS>(&sp->aux);
-      if (pos >= A_KEPT_MAX) continue;
-      const unsigned long long v = tl64<LDS>(&sp->val);
-      if (pack(okey(a.x), a.arc) == v) hist[out_base + pos].prev = a.src;
-      if (D.lattice_on && a.x <= cutoff_eff) {
-        const float extra = a.x - key2f((uint32_t)(v >> 32));
-        if (extra <= D.lattice_beam) emit_lat(a.arc, extra);
+    for (uint32_t i0 = 0; i0 < n_aux; i0 += NT * LAT_U) {
+      Aux a[LAT_U];
+#pragma unroll
+      for (int u = 0; u < LAT_U; ++u) {
+        const uint32_t i = i0 + u * NT + tid;
+        a[u] = i < n_aux ? aux[i] : Aux{0xFFFFFFFFu, 0.f, 0u, 0u};
       }
-    }
-    for (uint32_t j = tid; j < n_out; j += NT) {
-      const HTok t = hist[out_base + j];
-      if (!(t.handle & HAS_EPS)) continue;
-      const uint32_t h = t.handle & HMASK;
-      const uint32_t ne = rec[3 * (size_t)h], np = rec[3 * (size_t)h + 1];
-      for (uint32_t k = 0; k < np; ++k) {
-        const uint32_t r = h + 1 + ne + k;
-        const uint32_t *a = rec + 3 * (size_t)r;
-        const float x = t.cost + __uint_as_float(a[1]);
-        if (!(x <= cutoff_eff)) continue;
-        const int sl = ht_find<LDS>(slots, mask, hbits, a[0] & HMASK);
-        if (sl < 0) continue;
-        const Slot *sp = slots + sl;
-        const uint32_t pos = tl32<LDS>(&sp->aux);
-        if (pos >= A_KEPT_MAX) continue;
-        const unsigned long long v = tl64<LDS>(&sp->val);
-        if (pack(okey(x), r) == v) hist[out_base + pos].prev = j | PREV_SAME;
-        if (D.lattice_on) {
-          const float extra = x - key2f((uint32_t)(v >> 32));
-          if (extra <= D.lattice_beam) emit_lat(r, extra);
+#pragma unroll
+      for (int u = 0; u < LAT_U; ++u) {
+        if (a[u].slot == 0xFFFFFFFFu) continue;
+        if (!(a[u].slot & AUX_EPS)) {
+          // emitting candidate {slot of the destination, x, arc, index of the source token}
+          const Slot *sp = slots + a[u].slot;
+          const uint32_t pos = tl32<LDS>(&sp->aux);
+          if (pos >= A_KEPT_MAX) continue;
+          const unsigned long long v = tl64<LDS>(&sp->val);
+          if (pack(okey(a[u].x), a[u].arc) == v) hist[out_base + pos].prev = a[u].src;
+          if (D.lattice_on && a[u].x <= cutoff_eff) {
+            const float extra = a[u].x - key2f((uint32_t)(v >> 32));
+            if (extra <= D.lattice_beam) emit_lat(a[u].arc, extra);
+          }
+        } else {
+          // epsilon arc {slot of the source | AUX_EPS, weight, arc, handle of the destination}
+          const Slot *ss = slots + (a[u].slot & ~AUX_EPS);
+          const uint32_t spos = tl32<LDS>(&ss->aux);
+          if (spos >= A_KEPT_MAX) continue;                        // the source token was not kept
+          const float x = key2f((uint32_t)(tl64<LDS>(&ss->val) >> 32)) + a[u].x;
+          if (!(x <= cutoff_eff)) continue;
+          const int sl = ht_find<LDS>(slots, mask, hbits, a[u].src);
+          if (sl < 0) continue;
+          const Slot *sp = slots + sl;
+          const uint32_t pos = tl32<LDS>(&sp->aux);
+          if (pos >= A_KEPT_MAX) continue;
+          const unsigned long long v = tl64<LDS>(&sp->val);
+          if (pack(okey(x), a[u].arc) == v) hist[out_base + pos].prev = spos | PREV_SAME;
+          if (D.lattice_on) {
+            const float extra = x - key2f((uint32_t)(v >> 32));
+            if (extra <= D.lattice_beam) emit_lat(a[u].arc, extra);
+          }
         }
       }
     }
@@ -510,14 +552,13 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
   PHASE_MARK(3);
 
   // ---- 6. clear the table ---------------------------------------------------------------
-  if (LDS) {
-    for (int i = tid; i < LDS_SLOTS; i += NT) slots[i] = fresh;
-  } else if (S.flags & F_TOKOVF) {
-    for (uint32_t i = tid; i < D.H; i += NT) slots[i] = fresh;      // untracked claims: wipe everything
+  if (S.flags & F_TOKOVF) {                                        // untracked claims: wipe everything
+    const uint32_t n_all = LDS ? (uint32_t)LDS_SLOTS : D.H;
+    for (uint32_t i = tid; i < n_all; i += NT) slots[i] = fresh;
   } else {
     for (uint32_t i = tid; i < n_q; i += NT) {
-      const uint32_t e = queue[i];
-      if (!(e & Q_DUP)) slots[e & Q_SLOT] = fresh;
+      uint32_t sl, eps;
+      if (token_slot(i, sl, eps)) slots[sl] = fresh;
     }
   }
   if (tid == 0) {
@@ -534,7 +575,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
     S.max_post = max(S.max_post, (int)n_out);
     S.iters_max = max(S.iters_max, iters);
 #ifdef WFST_PHASE_TIMING
-    S.ph[7] += iters;
+    S.ph[7] += iters; S.dbg_tok += n_out; S.dbg_iters += iters; S.dbg_arcs += S.emit_arcs + S.eps_arcs;
 #endif
     if (abort_code != 0) S.status = abort_code;
   }
@@ -545,7 +586,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
 
 // One workgroup per lane.  is_init: (re)start the lane's channel and write frame 0.
 template <int NT>
-__global__ void __launch_bounds__(NT) k_advance(DecDev D, const LaneParam *__restrict__ lanes, int is_init) {
+__global__ void __launch_bounds__(NT, 4) k_advance(DecDev D, const LaneParam *__restrict__ lanes, int is_init) {
   __shared__ LaneShared<NT> S;
   const int tid = threadIdx.x;
   const LaneParam lp = lanes[blockIdx.x];
@@ -572,7 +613,8 @@ __global__ void __launch_bounds__(NT) k_advance(DecDev D, const LaneParam *__res
       S.max_post = cs->max_post; S.iters_max = cs->closure_iters_max;
     }
 #ifdef WFST_PHASE_TIMING
-    for (int k = 0; k < 8; ++k) S.ph[k] = 0;
+    for (int k = 0; k < 16; ++k) S.ph[k] = 0;
+    S.dbg_tok = 0; S.dbg_iters = 0; S.dbg_arcs = 0;
     S.tlast = wall_clock64();
 #endif
   }
@@ -604,10 +646,14 @@ __global__ void __launch_bounds__(NT) k_advance(DecDev D, const LaneParam *__res
 #ifdef WFST_PHASE_TIMING
     if (D.dbg) {
       for (int k = 0; k < 8; ++k) atomicAdd(D.dbg + k, S.ph[k]);
+      for (int k = 8; k < 16; ++k) atomicAdd(D.dbg + 8 + 8000 + k, S.ph[k]);
       unsigned long long tot = 0;
       for (int k = 0; k < 5; ++k) tot += S.ph[k];
+      for (int k = 8; k < 16; ++k) tot += S.ph[k];
       D.dbg[8 + blockIdx.x] = tot;                      // this lane's time for the call
-      D.dbg[8 + 4096 + blockIdx.x] = (unsigned long long)(S.hist_used);
+      D.dbg[8 + 2048 + blockIdx.x] = S.dbg_tok;
+      D.dbg[8 + 4096 + blockIdx.x] = S.dbg_iters;
+      D.dbg[8 + 6144 + blockIdx.x] = S.dbg_arcs;
     }
 #endif
   }
