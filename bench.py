@@ -99,8 +99,8 @@ def main() -> int:
         ptrs = row0 + np.uint64(i * chunk * P * 4)
         dec.advance_ptrs(ch_np, ptrs, strides_np, nfr_np, stream)
         if readout:
-            paths = dec.best_path_batch(chans, use_final=False, words_cap=1024)
-            offs = dec.lattice_arcs_batch(chans, out_device=lat_buf)
+            paths = dec.best_path_batch(ch_np, use_final=False, words_cap=1024, raw=True)
+            offs = dec.lattice_arcs_batch(ch_np, out_device=lat_buf)
             return paths, offs
         return None
 

@@ -104,6 +104,7 @@ typedef struct {
                                    a frame starts from plus the non-emitting out-degrees of
                                    the tokens within the beam after the closure             */
   int64_t lattice_arcs;         /* lattice arcs produced so far (read out or not)           */
+  int64_t tokens;               /* tokens kept, summed over all frames                      */
   int32_t max_tokens_pre_prune; /* largest token count after the closure                    */
   int32_t max_tokens;           /* largest token count kept                                 */
   int32_t closure_iters_max;    /* most closure rounds in one frame (diagnostic only)       */

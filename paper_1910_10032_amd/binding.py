@@ -45,7 +45,7 @@ class wfst_config_t(C.Structure):
 
 class wfst_stats_t(C.Structure):
     _fields_ = [("frames", C.c_int64), ("arcs_expanded", C.c_int64), ("lattice_arcs", C.c_int64),
-                ("max_tokens_pre_prune", C.c_int32), ("max_tokens", C.c_int32),
+                ("tokens", C.c_int64), ("max_tokens_pre_prune", C.c_int32), ("max_tokens", C.c_int32),
                 ("closure_iters_max", C.c_int32), ("status", C.c_int32)]
 
 
@@ -196,10 +196,19 @@ class WfstDecoder:
                                          strides.ctypes.data, n_frames.ctypes.data, C.c_void_p(stream)),
                "wfst_decode_advance")
 
-    def best_path_batch(self, channels, use_final: bool = True, words_cap: int = 4096):
-        """Per channel: dict(status, words, total_cost, reached_final)."""
+    def best_path_batch(self, channels, use_final: bool = True, words_cap: int = 4096, raw: bool = False):
+        """Per channel: dict(status, words, total_cost, reached_final); with raw=True the
+        arrays (words [n, cap], n_words, total_cost, reached_final, status) as filled by the call."""
         ch = np.ascontiguousarray(channels, np.int32)
         n = len(ch)
+        if raw:
+            words = np.empty((n, max(words_cap, 1)), np.int32)
+            nw, tc = np.empty(n, np.int32), np.empty(n, np.float32)
+            rf, st = np.empty(n, np.int32), np.empty(n, np.int32)
+            _check(lib().wfst_decode_best_path_batch(self.h, ch.ctypes.data, n, int(use_final), words.ctypes.data,
+                                                     words_cap, nw.ctypes.data, tc.ctypes.data, rf.ctypes.data,
+                                                     st.ctypes.data), "wfst_decode_best_path_batch")
+            return words, nw, tc, rf, st
         while True:
             words = np.zeros((n, max(words_cap, 1)), np.int32)
             nw, tc = np.zeros(n, np.int32), np.zeros(n, np.float32)

@@ -47,6 +47,7 @@ struct wfst_decoder {
   hipEvent_t param_ev[PARAM_RING] = {};
   int ring_pos = 0;
   int32_t *d_chans = nullptr;           // readout scratch [max(num_channels, max_lanes)]
+  std::vector<int32_t> staged_chans;    // what d_chans currently holds
   PathOut *d_pathout = nullptr;
   void *d_stage = nullptr; size_t stage_bytes = 0;
   unsigned long long *d_cnt = nullptr;
@@ -252,6 +253,10 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
   if (!rc) rc = dev_alloc(d, &D.frame_off, nc * (size_t)(c.max_frames + 2));
   if (!rc) rc = dev_alloc(d, &D.hist, nc * (size_t)D.hist_cap);
   if (!rc) rc = dev_alloc(d, &D.lat, nc * (size_t)D.lat_cap);
+  D.pc_wcap = 4 * (c.max_frames + 1) + 64;
+  if (!rc) rc = dev_alloc(d, &D.pc_entry, nc * (size_t)(c.max_frames + 2));
+  if (!rc) rc = dev_alloc(d, &D.pc_wcount, nc * (size_t)(c.max_frames + 2));
+  if (!rc) rc = dev_alloc(d, &D.pc_words, nc * (size_t)D.pc_wcap);
   d->per_channel_bytes = d->total_bytes / (int64_t)nc;
   const int64_t before_lanes = d->total_bytes;
   if (!rc) rc = dev_alloc(d, &D.slots, nl * (size_t)D.H);
@@ -352,6 +357,14 @@ int wfst_decode_advance(wfst_decoder_t *d, const int32_t *channels, int32_t n_la
   return launch_lanes(d, lp, 0, (hipStream_t)stream);
 }
 
+// Copy the channel list to the device unless it is the one already there.
+static int stage_channels(wfst_decoder *d, const int32_t *channels, int32_t n) {
+  if ((int32_t)d->staged_chans.size() == n && std::memcmp(d->staged_chans.data(), channels, sizeof(int32_t) * (size_t)n) == 0) return 0;
+  HIP_TRY(hipMemcpy(d->d_chans, channels, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
+  d->staged_chans.assign(channels, channels + n);
+  return 0;
+}
+
 int wfst_decode_best_path_batch(wfst_decoder_t *d, const int32_t *channels, int32_t n, int32_t use_final,
                                 int32_t *words, int32_t words_cap, int32_t *n_words, float *total_cost,
                                 int32_t *reached_final, int32_t *status) {
@@ -363,23 +376,35 @@ int wfst_decode_best_path_batch(wfst_decoder_t *d, const int32_t *channels, int3
   HIP_TRY(hipDeviceSynchronize());
   rc = ensure_stage(d, sizeof(int32_t) * (size_t)n * (size_t)std::max(words_cap, 1));
   if (rc) return rc;
-  HIP_TRY(hipMemcpy(d->d_chans, channels, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
-  hipLaunchKernelGGL(k_best_path, dim3(n), dim3(64), 0, 0, d->dev, (const int32_t *)d->d_chans, use_final,
-                     words_cap > 0 ? (int32_t *)d->d_stage : nullptr, words_cap, (uint32_t *)nullptr, 0, d->d_pathout);
+  rc = stage_channels(d, channels, n);
+  if (rc) return rc;
+  HIP_TRY(hipMemsetAsync(d->d_cnt, 0, sizeof(unsigned long long), 0));
+  hipLaunchKernelGGL(k_best_path_words, dim3(n), dim3(64), 0, 0, d->dev, (const int32_t *)d->d_chans, use_final,
+                     (int32_t *)d->d_stage, words_cap, d->d_cnt, d->d_pathout);
   HIP_TRY(hipGetLastError());
   std::vector<PathOut> po((size_t)n);
   HIP_TRY(hipMemcpy(po.data(), d->d_pathout, sizeof(PathOut) * (size_t)n, hipMemcpyDeviceToHost));
-  std::vector<int32_t> w;
-  if (words_cap > 0) {
-    w.resize((size_t)n * (size_t)words_cap);
-    HIP_TRY(hipMemcpy(w.data(), d->d_stage, sizeof(int32_t) * w.size(), hipMemcpyDeviceToHost));
-  }
+  long long used = 0;
+  for (int32_t i = 0; i < n; ++i) if (po[i].status == 0) used = std::max(used, po[i].word_off + po[i].n_words);
+  std::vector<int32_t> w((size_t)used);
+  if (used > 0) HIP_TRY(hipMemcpy(w.data(), d->d_stage, sizeof(int32_t) * (size_t)used, hipMemcpyDeviceToHost));
   for (int32_t i = 0; i < n; ++i) {
+    if (po[i].status == WFST_E_CAPACITY && po[i].n_words <= words_cap) {
+      // the remembered-path scratch was too small for this path: trace it in full instead
+      int32_t ch = channels[i];
+      HIP_TRY(hipMemcpy(d->d_chans, &ch, sizeof(int32_t), hipMemcpyHostToDevice));
+      d->staged_chans.clear();
+      hipLaunchKernelGGL(k_best_path, dim3(1), dim3(64), 0, 0, d->dev, (const int32_t *)d->d_chans, use_final,
+                         (int32_t *)d->d_stage, words_cap, (uint32_t *)nullptr, 0, d->d_pathout);
+      HIP_TRY(hipGetLastError());
+      HIP_TRY(hipMemcpy(&po[i], d->d_pathout, sizeof(PathOut), hipMemcpyDeviceToHost));
+      if (po[i].status == 0 && po[i].n_words > 0)
+        HIP_TRY(hipMemcpy(words + (size_t)i * words_cap, (int32_t *)d->d_stage + (words_cap - po[i].n_words),
+                          sizeof(int32_t) * (size_t)po[i].n_words, hipMemcpyDeviceToHost));
+    } else if (po[i].status == 0 && po[i].n_words > 0) {
+      std::memcpy(words + (size_t)i * words_cap, w.data() + po[i].word_off, sizeof(int32_t) * (size_t)po[i].n_words);
+    }
     status[i] = po[i].status; n_words[i] = po[i].n_words; total_cost[i] = po[i].total_cost; reached_final[i] = po[i].reached_final;
-    if (po[i].status == 0 && words_cap > 0 && po[i].n_words > 0)
-      std::memcpy(words + (size_t)i * words_cap, w.data() + (size_t)i * words_cap + (words_cap - po[i].n_words),
-                  sizeof(int32_t) * (size_t)po[i].n_words);
-    if (po[i].status == 0 && po[i].n_words > words_cap) status[i] = WFST_E_CAPACITY;
   }
   return 0;
 }
@@ -405,6 +430,7 @@ int wfst_decode_best_path_arcs(wfst_decoder_t *d, int32_t channel, int32_t use_f
   rc = ensure_stage(d, sizeof(uint32_t) * (size_t)std::max(cap, 1));
   if (rc) return rc;
   HIP_TRY(hipMemcpy(d->d_chans, &channel, sizeof(int32_t), hipMemcpyHostToDevice));
+  d->staged_chans.clear();
   hipLaunchKernelGGL(k_best_path, dim3(1), dim3(64), 0, 0, d->dev, (const int32_t *)d->d_chans, use_final,
                      (int32_t *)nullptr, 0, cap > 0 ? (uint32_t *)d->d_stage : nullptr, cap, d->d_pathout);
   HIP_TRY(hipGetLastError());
@@ -463,15 +489,13 @@ int wfst_decode_lattice_arcs_batch(wfst_decoder_t *d, const int32_t *channels, i
   int rc = check_channels(d, channels, n, true);
   if (rc) return rc;
   HIP_TRY(hipDeviceSynchronize());
-  HIP_TRY(hipMemcpy(d->d_chans, channels, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
-  hipLaunchKernelGGL(k_lattice_counts, dim3((n + 255) / 256), dim3(256), 0, 0, d->dev, (const int32_t *)d->d_chans, n, d->d_offs);
+  rc = stage_channels(d, channels, n);
+  if (rc) return rc;
+  hipLaunchKernelGGL(k_lattice_offsets, dim3(1), dim3(1024), 0, 0, d->dev, (const int32_t *)d->d_chans, n, d->d_offs);
   HIP_TRY(hipGetLastError());
-  std::vector<long long> cnt((size_t)n), offs((size_t)n + 1);
-  HIP_TRY(hipMemcpy(cnt.data(), d->d_offs, sizeof(long long) * (size_t)n, hipMemcpyDeviceToHost));
-  offs[0] = 0;
-  for (int32_t i = 0; i < n; ++i) offs[i + 1] = offs[i] + cnt[i];
-  const long long total = offs[n];
-  for (int32_t i = 0; i <= n; ++i) offsets[i] = offs[i];
+  static_assert(sizeof(long long) == sizeof(int64_t), "offset width");
+  HIP_TRY(hipMemcpy(offsets, d->d_offs, sizeof(long long) * ((size_t)n + 1), hipMemcpyDeviceToHost));
+  const long long total = offsets[n];
   if (total > cap) return WFST_E_CAPACITY;
   if (total > 0) {
     LatRec *dst = (LatRec *)out;
@@ -480,7 +504,6 @@ int wfst_decode_lattice_arcs_batch(wfst_decoder_t *d, const int32_t *channels, i
       if (rc) return rc;
       dst = (LatRec *)d->d_stage;
     }
-    HIP_TRY(hipMemcpy(d->d_offs, offs.data(), sizeof(long long) * ((size_t)n + 1), hipMemcpyHostToDevice));
     hipLaunchKernelGGL(k_export_lattice_batch, dim3(n, 8), dim3(256), 0, 0, d->dev, (const int32_t *)d->d_chans,
                        (const long long *)d->d_offs, dst);
     HIP_TRY(hipGetLastError());
@@ -523,7 +546,7 @@ int wfst_decode_stats(wfst_decoder_t *d, int32_t channel, wfst_stats_t *out) {
   ChanState cs;
   rc = read_chan(d, channel, &cs);
   if (rc) return rc;
-  out->frames = cs.num_frames; out->arcs_expanded = cs.arcs_expanded; out->lattice_arcs = cs.lat_total;
+  out->frames = cs.num_frames; out->arcs_expanded = cs.arcs_expanded; out->lattice_arcs = cs.lat_total; out->tokens = cs.hist_used;
   out->max_tokens_pre_prune = cs.max_pre; out->max_tokens = cs.max_post; out->closure_iters_max = cs.closure_iters_max;
   out->status = cs.status;
   return 0;

@@ -72,7 +72,8 @@ struct ChanState {
   long long lat_count;       // lattice records buffered
   long long lat_total;       // lattice records produced since init
   long long arcs_expanded;
-  int32_t max_pre, max_post, closure_iters_max, pad;
+  int32_t max_pre, max_post, closure_iters_max;
+  int32_t path_nf;           // frames covered by the remembered best path (0 = none)
 };
 
 struct LaneParam {
@@ -91,6 +92,11 @@ struct DecDev {
   Aux *aux;                  // [max_lanes][auxcap]
   uint32_t *dkey;            // [max_lanes][tokcap] dense cost keys for the selection
   uint32_t *dslot;           // [max_lanes][tokcap]
+  int32_t *pc_entry;         // [num_channels][max_frames + 2] remembered best path: token through
+                             // which it entered each frame
+  int32_t *pc_wcount;        // [num_channels][max_frames + 2] its words up to (and with) that arc
+  int32_t *pc_words;         // [num_channels][pc_wcap] its words; the tail is scratch for a trace
+  int32_t pc_wcap;
   long long hist_cap, lat_cap;
   uint32_t H;
   int32_t hbits, qcap, auxcap, tokcap, max_frames, max_active, lattice_on;

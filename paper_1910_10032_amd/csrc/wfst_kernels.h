@@ -643,6 +643,7 @@ __global__ void __launch_bounds__(NT, 4) k_advance(DecDev D, const LaneParam *__
     cs->status = S.status; cs->num_frames = S.nf; cs->hist_used = S.hist_used; cs->lat_count = S.lat_count;
     cs->lat_total = S.lat_total; cs->arcs_expanded = S.arcs_expanded; cs->max_pre = S.max_pre;
     cs->max_post = S.max_post; cs->closure_iters_max = S.iters_max;
+    if (is_init) cs->path_nf = 0;
 #ifdef WFST_PHASE_TIMING
     if (D.dbg) {
       for (int k = 0; k < 8; ++k) atomicAdd(D.dbg + k, S.ph[k]);
@@ -665,26 +666,21 @@ __global__ void k_fill_slots(Slot *slots, size_t n) {
 }
 
 // ---- readouts ----------------------------------------------------------------------------
-struct PathOut { int32_t status, n_words, n_arcs, reached_final; float total_cost; };
+struct PathOut { int32_t status, n_words, n_arcs, reached_final; float total_cost; int32_t pad; long long word_off; };
 
-// One wave per requested channel: arg-min over the last frame, then one lane follows the
-// back-pointers.  Words / arcs are written right-aligned into the channel's cap-sized
-// region, so a single backward walk leaves them in path order.
-__global__ void __launch_bounds__(64) k_best_path(DecDev D, const int32_t *chans, int use_final,
-                                                  int32_t *words, int words_cap, uint32_t *arcs, int arcs_cap,
-                                                  PathOut *out) {
-  const int ch = chans[blockIdx.x];
+// Arg-min over the last frame of a channel by the whole wave: packed (ordered cost, handle)
+// minimum over all tokens and, if asked for, over tokens in final states (cost + final cost).
+// Returns false if the channel has an error or no token; lane 0 gets the start of the walk.
+__device__ __forceinline__ bool path_start(const DecDev &D, int ch, int use_final, PathOut &po, int &F, int &cur) {
   const int lane = threadIdx.x;
   const ChanState *cs = D.chan + ch;
   const long long *foff = D.frame_off + (size_t)ch * (size_t)(D.max_frames + 2);
   const HTok *hist = D.hist + (size_t)ch * (size_t)D.hist_cap;
   const uint32_t *rec = D.g.rec;
-  PathOut po{0, 0, 0, 0, 0.f};
-  if (cs->status != 0) { if (lane == 0) { po.status = cs->status; out[blockIdx.x] = po; } return; }
-  const int F = cs->num_frames - 1;
+  if (cs->status != 0) { po.status = cs->status; return false; }
+  F = cs->num_frames - 1;
   const long long o = foff[F];
   const int n = (int)(foff[F + 1] - o);
-  // packed (ordered cost, handle) minimum; final states first if asked for
   unsigned long long bf = ~0ull, bn = ~0ull; int bfi = -1, bni = -1;
   for (int i = lane; i < n; i += 64) {
     const HTok t = hist[o + i];
@@ -705,11 +701,27 @@ __global__ void __launch_bounds__(64) k_best_path(DecDev D, const int32_t *chans
     o2 = __shfl_xor(bf, d, 64); i2 = __shfl_xor(bfi, d, 64);
     if (o2 < bf) { bf = o2; bfi = i2; }
   }
-  if (lane != 0) return;
-  if (n == 0) { po.status = E_DEAD_CHANNEL; out[blockIdx.x] = po; return; }
-  int cur;
+  if (n == 0) { po.status = E_DEAD_CHANNEL; return false; }
   if (use_final && bfi >= 0) { cur = bfi; po.total_cost = key2f((uint32_t)(bf >> 32)); po.reached_final = 1; }
   else { cur = bni; po.total_cost = key2f((uint32_t)(bn >> 32)); }
+  return true;
+}
+
+// Best path of one channel with its arcs (one wave; lane 0 follows the back-pointers over the
+// whole utterance).  Words / arcs are written right-aligned into cap-sized regions, so a
+// single backward walk leaves them in path order.
+__global__ void __launch_bounds__(64) k_best_path(DecDev D, const int32_t *chans, int use_final,
+                                                  int32_t *words, int words_cap, uint32_t *arcs, int arcs_cap,
+                                                  PathOut *out) {
+  const int ch = chans[blockIdx.x];
+  const ChanState *cs = D.chan + ch;
+  const long long *foff = D.frame_off + (size_t)ch * (size_t)(D.max_frames + 2);
+  const HTok *hist = D.hist + (size_t)ch * (size_t)D.hist_cap;
+  PathOut po{0, 0, 0, 0, 0.f, 0, 0};
+  int F = 0, cur = 0;
+  const bool ok = path_start(D, ch, use_final, po, F, cur);
+  if (threadIdx.x != 0) return;
+  if (!ok) { out[blockIdx.x] = po; return; }
   int32_t *wout = words ? words + (size_t)blockIdx.x * words_cap : nullptr;
   uint32_t *aout = arcs ? arcs + (size_t)blockIdx.x * arcs_cap : nullptr;
   int f = F, nw = 0, na = 0;
@@ -729,6 +741,77 @@ __global__ void __launch_bounds__(64) k_best_path(DecDev D, const int32_t *chans
   po.n_words = nw; po.n_arcs = na;
   if (po.status == 0 && ((wout && nw > words_cap) || (aout && na > arcs_cap))) po.status = E_CAPACITY;
   out[blockIdx.x] = po;
+}
+
+// Best-path words of many channels (one wave each).  Back-pointers are unique, so two best
+// paths that share a token share everything before it: each channel remembers, per frame,
+// the token through which its last traced path entered the frame and the words up to there;
+// a new trace walks back only until it meets the remembered path (a chunk of frames plus the
+// distance to the merge point, not the whole utterance) and splices the remembered prefix.
+// Words of all channels are packed into `words` at po.word_off (allotted with one atomic add).
+__global__ void __launch_bounds__(64) k_best_path_words(DecDev D, const int32_t *chans, int use_final, int32_t *words,
+                                                        int words_cap, unsigned long long *words_used, PathOut *out) {
+  const int ch = chans[blockIdx.x];
+  const int lane = threadIdx.x;
+  ChanState *cs = D.chan + ch;
+  const long long *foff = D.frame_off + (size_t)ch * (size_t)(D.max_frames + 2);
+  const HTok *hist = D.hist + (size_t)ch * (size_t)D.hist_cap;
+  int32_t *entry = D.pc_entry + (size_t)ch * (size_t)(D.max_frames + 2);
+  int32_t *wcount = D.pc_wcount + (size_t)ch * (size_t)(D.max_frames + 2);
+  int32_t *cw = D.pc_words + (size_t)ch * (size_t)D.pc_wcap;
+  __shared__ int sh[4];                      // status, total words, merge frame, F
+  PathOut po{0, 0, 0, 0, 0.f, 0, 0};
+  int F = 0, cur = 0;
+  const bool ok = path_start(D, ch, use_final, po, F, cur);
+  if (!ok) { if (lane == 0) out[blockIdx.x] = po; return; }
+  if (lane == 0) {
+    const int cached_nf = cs->path_nf;
+    int f = F, k = 0, base = 0, merge_f = 0, status = 0;
+    const long long max_steps = cs->hist_used + 1;
+    for (long long step = 0;; ++step) {
+      if (cur < 0 || (long long)cur >= foff[f + 1] - foff[f]) { status = E_BROKEN_TRACE; break; }
+      const HTok t = hist[foff[f] + cur];
+      if (t.in_arc == NO_ARC) break;
+      if (t.prev == NO_ARC || step > max_steps) { status = E_BROKEN_TRACE; break; }
+      const bool is_entry = !(t.prev & PREV_SAME);
+      if (is_entry) {
+        if (f < cached_nf && entry[f] == cur) { base = wcount[f]; merge_f = f; break; }
+        entry[f] = cur; wcount[f] = k;        // k: words found so far, all later on the path; fixed up below
+      }
+      const int32_t w = D.g.label[t.in_arc];
+      if (w != 0) {
+        if (k < D.pc_wcap) cw[D.pc_wcap - 1 - k] = w;
+        ++k;
+      }
+      if (is_entry) { cur = (int)t.prev; --f; if (f < 0) { status = E_BROKEN_TRACE; break; } }
+      else cur = (int)(t.prev & ~PREV_SAME);
+    }
+    if (status == 0 && (long long)base + 2ll * k > (long long)D.pc_wcap) status = E_CAPACITY;
+    sh[0] = status; sh[1] = base + k; sh[2] = merge_f; sh[3] = k;
+  }
+  __syncthreads();
+  const int status = sh[0], total = sh[1], merge_f = sh[2], k = sh[3];
+  if (status != 0) {
+    if (lane == 0) { cs->path_nf = 0; po.status = status; po.n_words = total; out[blockIdx.x] = po; }
+    return;
+  }
+  for (int f = merge_f + 1 + lane; f <= F; f += 64) wcount[f] = total - wcount[f];
+  const int base = total - k;
+  for (int j = lane; j < k; j += 64) cw[base + j] = cw[D.pc_wcap - k + j];
+  __syncthreads();
+  if (lane == 0) {
+    cs->path_nf = F + 1;
+    po.n_words = total;
+    if (total > words_cap) po.status = E_CAPACITY;
+    else po.word_off = (long long)atomicAdd(words_used, (unsigned long long)total);
+    sh[0] = po.status;
+    *(long long *)&sh[2] = po.word_off;
+    out[blockIdx.x] = po;
+  }
+  __syncthreads();
+  if (sh[0] != 0) return;
+  const long long off = *(long long *)&sh[2];
+  for (int j = lane; j < total; j += 64) words[off + j] = cw[j];
 }
 
 // Tokens of one frame in the public form: state id and caller's arc id.
@@ -757,13 +840,35 @@ __global__ void k_reset_lattice(DecDev D, int ch) { D.chan[ch].lat_count = 0; }
 
 // Batched drain: counts of the listed channels, then one copy kernel (grid.x = channel,
 // grid.y = slices of that channel's buffer), then the reset.
-__global__ void k_lattice_counts(DecDev D, const int32_t *chans, int n, long long *counts) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) {
+// offs[0..n]: exclusive prefix sums of the buffered record counts of the listed channels
+// (channels stopped by an overflow count as empty).  One block.
+__global__ void __launch_bounds__(1024) k_lattice_offsets(DecDev D, const int32_t *chans, int n, long long *offs) {
+  __shared__ long long part[1024];
+  const int tid = threadIdx.x;
+  const int per = (n + 1023) / 1024;
+  const int b = tid * per, e = min(n, b + per);
+  long long sum = 0;
+  for (int i = b; i < e; ++i) {
     const ChanState *cs = D.chan + chans[i];
     const bool readable = cs->status == 0 || cs->status == E_DEAD_CHANNEL || cs->status == E_NAN_INPUT;
-    counts[i] = readable ? cs->lat_count : 0;
+    sum += readable ? cs->lat_count : 0;
   }
+  part[tid] = sum;
+  __syncthreads();
+  for (int d = 1; d < 1024; d <<= 1) {
+    const long long v = tid >= d ? part[tid - d] : 0;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  long long run = part[tid] - sum;
+  for (int i = b; i < e; ++i) {
+    const ChanState *cs = D.chan + chans[i];
+    const bool readable = cs->status == 0 || cs->status == E_DEAD_CHANNEL || cs->status == E_NAN_INPUT;
+    offs[i] = run;
+    run += readable ? cs->lat_count : 0;
+  }
+  if (tid == 1023) offs[n] = part[1023];
 }
 __global__ void k_export_lattice_batch(DecDev D, const int32_t *chans, const long long *offs, LatRec *out) {
   const int ch = chans[blockIdx.x];

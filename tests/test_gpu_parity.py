@@ -117,6 +117,42 @@ def test_config1_prefix(torch_cuda, B):
     compare_channel(dec, 0, ods[0], label="cfg1")
 
 
+def test_streaming_partial_best_paths(torch_cuda, B):
+    """Per-chunk best paths (Section 3: intermediate results during streaming): the batch call
+    remembers each channel's last path and re-traces only up to the merge point; every
+    partial result must equal the checker's full trace at the same point."""
+    c = synth.configs()[0]
+    g = synth.make_graph(c.graph)
+    n, T, chunk = 4, 120, 10
+    rows = [c.loglikes(s, 0, T) for s in range(n)]
+    gg = B.WfstGraph(g)
+    dec = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=n, max_lanes=n, max_frames=T,
+                        lattice_capacity=1 << 20)
+    chans = list(range(n))
+    dec.init_channels(chans)
+    dev = [torch_cuda.from_numpy(r).cuda() for r in rows]
+    og = oracle.OracleGraph(g)
+    ods = [oracle.OracleDecoder(og, c.beam, c.lattice_beam, c.max_active) for _ in range(n)]
+    for k, f0 in enumerate(range(0, T, chunk)):
+        dec.advance(chans, [d[f0:f0 + chunk] for d in dev])
+        for od, r in zip(ods, rows):
+            od.advance(r[f0:f0 + chunk])
+        for use_final in ((k % 2 == 0), True, False):
+            got = dec.best_path_batch(chans, use_final=use_final, words_cap=64 if k < 3 else 4096)
+            for ch, (r, od) in enumerate(zip(got, ods)):
+                want = od.best_path(use_final)
+                assert r["status"] == 0
+                assert np.array_equal(r["words"], want["words"]), f"chunk {k} ch {ch}"
+                assert np.float32(r["total_cost"]).view(np.uint32) == np.float32(want["total_cost"]).view(np.uint32)
+                assert r["reached_final"] == want["reached_final"]
+    # restarting a channel forgets its remembered path
+    dec.init_channels([1])
+    dec.advance([1], [dev[2][:30]])
+    od = oracle.OracleDecoder(og, c.beam, c.lattice_beam, c.max_active)
+    od.advance(rows[2][:30])
+    assert np.array_equal(dec.best_path_batch([1], use_final=False)[0]["words"], od.best_path(False)["words"])
+
+
 def test_dead_and_bad_scores(torch_cuda, B):
     rng = np.random.default_rng(5)
     g = random_graph(rng, num_states=30, n_emit_per_state=(1, 3), eps_prob=0.05, num_pdfs=5)
