@@ -26,11 +26,10 @@ sys.path.insert(0, ROOT)
 
 FRAME_SHIFT_S = 0.010
 HBM_PEAK_GBS = 8000.0
-# Algorithmic HBM bytes per expanded arc (derivation in DESIGN.md, "Algorithmic bytes"):
-# 12 B arc record + (12 B state header + 16 B token read) / 2.875 arcs per token
-# + 1 B of score row per arc + 16 B token written and 12 B lattice record per kept token
-# (about 0.35 kept tokens per arc) ~= 33 B.
-ALGO_BYTES_PER_ARC = 33.0
+# Algorithmic HBM bytes (what the method itself must move):
+BYTES_PER_ARC = 16.0      # 12-byte arc record + 4-byte score
+BYTES_PER_TOKEN = 44.0    # 12-byte state record + 16-byte token read when expanded + 16-byte token written
+BYTES_PER_LAT = 12.0      # one lattice record
 
 
 def main() -> int:
@@ -108,7 +107,8 @@ def main() -> int:
     for i in range(W):
         step(i, readout)
     torch.cuda.synchronize()
-    arcs0 = sum(dec.stats(c)["arcs_expanded"] for c in chans)
+    stats0 = [dec.stats(c) for c in chans]
+    arcs0 = sum(s["arcs_expanded"] for s in stats0)
     dec.set_profiling(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -126,9 +126,20 @@ def main() -> int:
     wall = t1 - t0
     audio_s = K * n_ch * chunk * FRAME_SHIFT_S
     rtfx = audio_s / wall
+    tokens = sum(s["tokens"] for s in stats) - sum(s["tokens"] for s in stats0)
+    lat_recs = sum(s["lattice_arcs"] for s in stats) - sum(s["lattice_arcs"] for s in stats0)
     avg_launch_s = kernel_ms / 1e3 / max(launches, 1)
-    arcs_per_launch = arcs / max(launches, 1)
-    achieved = ALGO_BYTES_PER_ARC * arcs_per_launch / avg_launch_s / 1e9
+    algo_bytes = BYTES_PER_ARC * arcs + BYTES_PER_TOKEN * tokens + BYTES_PER_LAT * lat_recs
+    achieved = algo_bytes / max(launches, 1) / avg_launch_s / 1e9
+
+    # HBM bytes per launch from the committed rocprofv3 counter runs (FETCH_SIZE / WRITE_SIZE,
+    # scaled by a plain copy of known size); not measurable from inside this process
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "k_advance_config3_traffic.json")
+    if os.path.exists(tpath) and n_ch == cfg.n_streams:
+        with open(tpath) as f:
+            tj = json.load(f)
+        traffic = tj["fetch_bytes_per_launch"] + tj["write_bytes_per_launch"]
 
     result = {
         "metric": "decode RTFx (audio s / wall s) + arcs expanded/s, batched streams, 1 GPU",
@@ -146,8 +157,9 @@ def main() -> int:
         "max_tokens_pre_prune": max(s["max_tokens_pre_prune"] for s in stats),
         "max_tokens": max(s["max_tokens"] for s in stats),
         "roofline": {"bound": "hbm", "kernel": "k_advance", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
-                     "algorithmic_bytes_per_arc": ALGO_BYTES_PER_ARC, "launches": launches,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic,
+                     "algorithmic_bytes_per_launch": round(algo_bytes / max(launches, 1)),
+                     "arcs_per_launch": round(arcs / max(launches, 1)), "launches": launches,
                      "avg_launch_ms": round(avg_launch_s * 1e3, 4)},
         "setup_s": round(t0 - t_setup, 1),
     }
