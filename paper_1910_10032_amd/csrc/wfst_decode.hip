@@ -270,8 +270,8 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
   if (!rc) rc = dev_alloc(d, &d->d_pathout, std::max(nc, nl));
   if (!rc) rc = dev_alloc(d, &d->d_cnt, 1);
 #ifdef WFST_PHASE_TIMING
-  if (!rc) rc = dev_alloc(d, &D.dbg, 8 + 8192);
-  if (!rc && hipMemset(D.dbg, 0, 8 * (8 + 8192)) != hipSuccess) rc = WFST_E_DEVICE;
+  if (!rc) rc = dev_alloc(d, &D.dbg, 8 + 16384);
+  if (!rc && hipMemset(D.dbg, 0, 8 * (8 + 16384)) != hipSuccess) rc = WFST_E_DEVICE;
 #endif
   if (!rc) rc = dev_alloc(d, &d->d_offs, std::max(nc, nl) + 1);
   if (!rc) {
@@ -556,8 +556,8 @@ int wfst_decode_stats(wfst_decoder_t *d, int32_t channel, wfst_stats_t *out) {
 // Instrumented builds only: summed per-phase wall-clock ticks (100 MHz) of workgroup leaders.
 int wfst_debug_phase_times(wfst_decoder_t *d, unsigned long long *out8, int reset) {
   HIP_TRY(hipDeviceSynchronize());
-  HIP_TRY(hipMemcpy(out8, d->dev.dbg, 8 * (8 + 8192), hipMemcpyDeviceToHost));
-  if (reset) HIP_TRY(hipMemset(d->dev.dbg, 0, 8 * (8 + 8192)));
+  HIP_TRY(hipMemcpy(out8, d->dev.dbg, 8 * (8 + 16384), hipMemcpyDeviceToHost));
+  if (reset) HIP_TRY(hipMemset(d->dev.dbg, 0, 8 * (8 + 16384)));
   return 0;
 }
 #endif

@@ -99,6 +99,7 @@ __device__ __forceinline__ int ht_find(const Slot *slots, uint32_t mask, int hbi
 // lane's table in global memory (nothing is committed before the contraction stage).
 constexpr int LDS_SLOTS = 4096, LDS_HBITS = 12, LDS_CLAIM_LIMIT = 3072, LDS_NIN_MAX = 1024;
 constexpr int EXP_U = 4;                   // arcs per thread and round of the emitting expansion
+constexpr int EPS_U = 2;                   // epsilon arcs of a token fetched together
 constexpr int LAT_U = 4;                   // candidate records per thread and round of the lattice stage
 constexpr uint32_t AUX_EPS = 0x80000000u;  // Aux::slot flag: the record is an epsilon arc
 constexpr int LDS_QCAP = 4096;             // entries of the LDS token queue (16-bit each)
@@ -358,46 +359,67 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
   const float cutoff = key2f(bestk) + D.beam;
 
   // ---- 2. non-emitting closure ----------------------------------------------------------
-  // expand the epsilon arcs of the token in slot `sp`, whose cost is within the cutoff
-  auto expand_eps = [&](uint32_t src_slot, float c) {
-    Slot *sp = slots + src_slot;
-    const uint32_t h = tl32<LDS>(&sp->handle);
-    const uint32_t ne = rec[3 * (size_t)h], np = rec[3 * (size_t)h + 1];
-    // first expansion of this token: count its arcs and note every one of them (source slot,
-    // weight, arc, destination) so that the lattice stage can re-derive the candidates from
-    // final costs without reading the graph again
-    const bool first = atomicAnd(&sp->aux, ~A_FRESH) & A_FRESH;
-    uint32_t ai = 0;
-    if (first) {
-      atomicAdd(&S.eps_arcs, (unsigned long long)np);
-      ai = atomicAdd(&S.auxn, np);
-      if (ai + np > (uint32_t)D.auxcap) atomicOr(&S.flags, F_LATOVF);
-    }
-    for (uint32_t k = 0; k < np; ++k) {
-      const uint32_t r = h + 1 + ne + k;
-      const uint32_t *a = rec + 3 * (size_t)r;
-      const uint32_t dw = a[0];
-      const float w = __uint_as_float(a[1]);
-      if (first && ai + k < (uint32_t)D.auxcap) aux[ai + k] = Aux{src_slot | AUX_EPS, w, r, dw & HMASK};
-      const float x = c + w;
-      if (!(x <= cutoff)) continue;
-      bool cl, im;
-      const int sl = ht_insert<LDS>(slots, mask, hbits, dw & HMASK, pack(okey(x), r), cl, im);
-      if (sl < 0) { atomicOr(&S.flags, LDS ? F_RESTART : F_TOKOVF); continue; }
-      if (cl || im) on_claim(sl, dw, !cl);
-    }
+  // One epsilon arc of an expanded token: note it for the lattice stage on the token's first
+  // expansion (source slot, weight, arc, destination), then offer the candidate.
+  auto relax_eps = [&](uint32_t src_slot, float c, uint32_t r, uint32_t dw, float w, uint32_t note_at) {
+    if (note_at < (uint32_t)D.auxcap) aux[note_at] = Aux{src_slot | AUX_EPS, w, r, dw & HMASK};
+    const float x = c + w;
+    if (!(x <= cutoff)) return;
+    bool cl, im;
+    const int sl = ht_insert<LDS>(slots, mask, hbits, dw & HMASK, pack(okey(x), r), cl, im);
+    if (sl < 0) { atomicOr(&S.flags, LDS ? F_RESTART : F_TOKOVF); return; }
+    if (cl || im) on_claim(sl, dw, !cl);
   };
   int iters = 0;
   if (abort_code == 0 && !(LDS && (S.flags & F_RESTART))) {
     uint32_t w0 = 0, w1 = min(S.qtail, qcap);
     __syncthreads();
     while (w0 < w1) {
-      for (uint32_t i = w0 + tid; i < w1; i += NT) {
-        uint32_t sl; bool eps, dup;
-        qget(i, sl, eps, dup);
-        if (!eps) continue;
-        const float c = key2f((uint32_t)(tl64<LDS>(&slots[sl].val) >> 32));
-        if (c <= cutoff) expand_eps(sl, c);
+      // every thread takes one queue entry of the window per pass; the pass is kept convergent
+      // (predicated, no early exit) so that the wave can allot note space with one atomic
+      for (uint32_t i0 = w0; i0 < w1; i0 += NT) {
+        const uint32_t i = i0 + tid;
+        bool act = false; uint32_t src = 0; float c = 0.f;
+        if (i < w1) {
+          bool eps, dup;
+          qget(i, src, eps, dup);
+          if (eps) { c = key2f((uint32_t)(tl64<LDS>(&slots[src].val) >> 32)); act = c <= cutoff; }
+        }
+        uint32_t h = 0, ne = 0, np = 0; bool first = false;
+        if (act) {
+          h = tl32<LDS>(&slots[src].handle);
+          ne = rec[3 * (size_t)h]; np = rec[3 * (size_t)h + 1];
+          first = atomicAnd(&slots[src].aux, ~A_FRESH) & A_FRESH;   // first expansion while within the cutoff
+        }
+        uint32_t dwv[EPS_U]; float wv[EPS_U];                        // the first arcs, loads in flight together
+#pragma unroll
+        for (int k = 0; k < EPS_U; ++k) {
+          dwv[k] = 0; wv[k] = 0.f;
+          if (act && (uint32_t)k < np) {
+            const uint32_t *a = rec + 3 * (size_t)(h + 1 + ne + k);
+            dwv[k] = a[0]; wv[k] = __uint_as_float(a[1]);
+          }
+        }
+        // note space and the arc count, one atomic per wave
+        const uint32_t nn = first ? np : 0u;
+        uint32_t inc = nn;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) { const uint32_t t = (uint32_t)__shfl_up((int)inc, d, 64); if ((tid & 63) >= d) inc += t; }
+        const uint32_t wave_total = (uint32_t)__shfl((int)inc, 63, 64);
+        uint32_t note = 0;
+        if ((tid & 63) == 0 && wave_total) {
+          note = atomicAdd(&S.auxn, wave_total);
+          atomicAdd(&S.eps_arcs, (unsigned long long)wave_total);
+          if (note + wave_total > (uint32_t)D.auxcap) atomicOr(&S.flags, F_LATOVF);
+        }
+        note = (uint32_t)__shfl((int)note, 0, 64) + inc - nn;
+#pragma unroll
+        for (int k = 0; k < EPS_U; ++k)
+          if (act && (uint32_t)k < np) relax_eps(src, c, h + 1 + ne + k, dwv[k], wv[k], first ? note + k : 0xFFFFFFFFu);
+        for (uint32_t k = EPS_U; act && k < np; ++k) {
+          const uint32_t *a = rec + 3 * (size_t)(h + 1 + ne + k);
+          relax_eps(src, c, h + 1 + ne + k, a[0], __uint_as_float(a[1]), first ? note + k : 0xFFFFFFFFu);
+        }
       }
       __syncthreads();
       PHASE_MARK(11);
@@ -652,6 +674,7 @@ __global__ void __launch_bounds__(NT, 4) k_advance(DecDev D, const LaneParam *__
       for (int k = 0; k < 5; ++k) tot += S.ph[k];
       for (int k = 8; k < 16; ++k) tot += S.ph[k];
       D.dbg[8 + blockIdx.x] = tot;                      // this lane's time for the call
+      if (blockIdx.x < 512) for (int k = 0; k < 16; ++k) D.dbg[8 + 8192 + blockIdx.x * 16 + k] = S.ph[k];
       D.dbg[8 + 2048 + blockIdx.x] = S.dbg_tok;
       D.dbg[8 + 4096 + blockIdx.x] = S.dbg_iters;
       D.dbg[8 + 6144 + blockIdx.x] = S.dbg_arcs;
