@@ -120,21 +120,35 @@ struct LaneShared {
   uint32_t sel_bin, sel_below, sel_cnt;
   unsigned long long emit_arcs, eps_arcs;
   // channel state, cached for the duration of the call
-  int status, nf, max_pre, max_post, iters_max;
-  long long hist_used, lat_count, lat_total, arcs_expanded;
+  int status, nf, max_pre, max_post, iters_max, n_in;
+  long long in_off, hist_used, lat_count, lat_total, arcs_expanded;
 #ifdef WFST_PHASE_TIMING
   unsigned long long ph[16], tlast, dbg_tok, dbg_iters, dbg_arcs;
 #endif
   uint16_t lq[LDS_QCAP];       // token queue of small frames
   Slot table[LDS_SLOTS];       // state table of small frames
 };
-static_assert(NBINS * 4 <= 512 * 12, "histogram must fit in the tile arrays");
 
 #ifdef WFST_PHASE_TIMING
 #define PHASE_MARK(k) do { if (threadIdx.x == 0) { unsigned long long t_ = wall_clock64(); S.ph[k] += t_ - S.tlast; S.tlast = t_; } } while (0)
 #else
 #define PHASE_MARK(k) do { } while (0)
 #endif
+
+// Workgroup barrier for stages that communicate through LDS only: it orders LDS accesses but
+// does not wait for global loads or stores in flight, so the score-row touch and the stores of
+// notes / tokens / lattice records keep travelling across it.  With LOCAL false it is an
+// ordinary __syncthreads() (the global-table path communicates through global memory).
+template <bool LOCAL>
+__device__ __forceinline__ void wg_sync() {
+  if (LOCAL) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  } else {
+    __syncthreads();
+  }
+}
 
 // One counter update per wavefront: the lanes that call this together (same call site,
 // any subset of the wave) get consecutive indices from a single atomic add.
@@ -148,7 +162,7 @@ __device__ __forceinline__ uint32_t wave_alloc(uint32_t *counter) {
   return base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
 }
 
-template <int NT>
+template <int NT, bool LOCAL = false>
 __device__ __forceinline__ int block_excl_scan(int v, int *s_wave, int &total) {
   const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
   int inc = v;
@@ -158,7 +172,7 @@ __device__ __forceinline__ int block_excl_scan(int v, int *s_wave, int &total) {
     if (lane >= d) inc += t;
   }
   if (lane == 63) s_wave[wid] = inc;
-  __syncthreads();
+  wg_sync<LOCAL>();
   int base = 0, tot = 0;
 #pragma unroll
   for (int i = 0; i < NT / 64; ++i) {
@@ -166,7 +180,7 @@ __device__ __forceinline__ int block_excl_scan(int v, int *s_wave, int &total) {
     if (i < wid) base += t;
     tot += t;
   }
-  __syncthreads();
+  wg_sync<LOCAL>();
   total = tot;
   return base + inc - v;
 }
@@ -231,7 +245,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
     S.qtail = 0; S.nclaim = 0; S.auxn = 0; S.best = KEY_NONE; S.flags = 0; S.nvalid = 0; S.nout = 0; S.latn = 0;
     S.kmin = 0xFFFFFFFFu; S.kmax = 0; S.emit_arcs = 0; S.eps_arcs = 0;
   }
-  __syncthreads();
+  wg_sync<LDS>();
   const int nf = S.nf;                       // index of the frame being written
   const long long out_base = S.hist_used;
   int abort_code = 0;
@@ -266,12 +280,13 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
         S.best = okey(0.0f);
       }
     } else {
-      const long long in_off = foff[nf - 1];
-      const int n_in = (int)(foff[nf] - in_off);
+      const long long in_off = S.in_off;
+      const int n_in = S.n_in;
       // touch this frame's row of scores (one 64-byte line per thread) while the tokens'
       // graph records are being fetched, so that the gathers by pdf id below hit L2
-      float touch = 0.f;
-      for (int p = tid * 16; p < D.g.num_pdfs; p += NT * 16) touch += ll[p];
+      const float touch = tid * 16 < D.g.num_pdfs ? ll[tid * 16] : 0.f;
+      float touch_more = 0.f;
+      for (int p = (NT + tid) * 16; p < D.g.num_pdfs; p += NT * 16) touch_more += ll[p];
       // this thread's token of a tile: state handle, cost, emitting out-degree
       auto load_token = [&](int i, uint32_t &h, float &c, int &ne) {
         ne = 0; h = 0; c = 0.f;
@@ -285,9 +300,9 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
       load_token(tid, h, c, ne);
       for (int tb = 0; tb < n_in; tb += NT) {
         int total;
-        const int ex = block_excl_scan<NT>(ne, S.wave_tmp, total);
+        const int ex = block_excl_scan<NT, LDS>(ne, S.wave_tmp, total);
         S.scan[tid] = ex; S.cost[tid] = c; S.base[tid] = h + 1;
-        __syncthreads();
+        wg_sync<LDS>();
         PHASE_MARK(8);
         if (tid == 0) S.emit_arcs += (unsigned long long)total;
         if (tb + NT < n_in) load_token(tb + NT + tid, hn, cn, nen);   // next tile, in flight during this one's rounds
@@ -322,7 +337,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
 #pragma unroll
           for (int d = 32; d; d >>= 1) m = min(m, (uint32_t)__shfl_xor((int)m, d, 64));
           if ((tid & 63) == 0 && m != KEY_NONE) atomicMin(&S.best, m);
-          __syncthreads();
+          wg_sync<LDS>();
           PHASE_MARK(9);
           const float cut = key2f(S.best) + D.beam;     // running bound, never below the final cutoff
 #pragma unroll
@@ -339,14 +354,14 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
             }
           }
         }
-        __syncthreads();
+        wg_sync<LDS>();
         PHASE_MARK(10);
         h = hn; c = cn; ne = nen;
       }
-      asm volatile("" ::"v"(touch));
+      asm volatile("" ::"v"(touch), "v"(touch_more));
     }
   }
-  __syncthreads();
+  wg_sync<LDS>();
   PHASE_MARK(0);
   const uint32_t bestk = S.best;
   if (abort_code == 0) {
@@ -373,7 +388,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
   int iters = 0;
   if (abort_code == 0 && !(LDS && (S.flags & F_RESTART))) {
     uint32_t w0 = 0, w1 = min(S.qtail, qcap);
-    __syncthreads();
+    wg_sync<LDS>();
     while (w0 < w1) {
       // every thread takes one queue entry of the window per pass; the pass is kept convergent
       // (predicated, no early exit) so that the wave can allot note space with one atomic
@@ -421,18 +436,18 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
           relax_eps(src, c, h + 1 + ne + k, a[0], __uint_as_float(a[1]), first ? note + k : 0xFFFFFFFFu);
         }
       }
-      __syncthreads();
+      wg_sync<LDS>();
       PHASE_MARK(11);
       w0 = w1; w1 = min(S.qtail, qcap);
       ++iters;
-      __syncthreads();
+      wg_sync<LDS>();
     }
     if (S.flags & F_TOKOVF) abort_code = E_TOKEN_OVERFLOW;
     else if (S.flags & F_LATOVF) abort_code = E_LATTICE_OVERFLOW;
   }
   PHASE_MARK(1);
   if (LDS) {
-    __syncthreads();
+    wg_sync<true>();
     if (abort_code == 0 && (S.flags & F_RESTART)) {     // outgrew the LDS table: wipe it, redo with the global one
       for (int i = tid; i < LDS_SLOTS; i += NT) slots[i] = fresh;
       __syncthreads();
@@ -467,7 +482,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
         hist[out_base + pos] = HTok{tl32<LDS>(&sp->handle) | (eps ? HAS_EPS : 0u), c, (uint32_t)v, NO_ARC};
         sp->aux = pos;
       }
-      __syncthreads();
+      wg_sync<LDS>();
       if (tid == 0) S.nvalid = S.nout;
     } else {
       for (uint32_t i = tid; i < n_q; i += NT) {
@@ -570,7 +585,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
       }
     }
   }
-  __syncthreads();
+  wg_sync<LDS>();
   PHASE_MARK(3);
 
   // ---- 6. clear the table ---------------------------------------------------------------
@@ -589,6 +604,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
     if (nf <= D.max_frames) {
       foff[nf + 1] = out_base + n_out;
       S.nf = nf + 1;
+      S.in_off = out_base; S.n_in = (int)n_out;      // the frame just written is what the next one expands
     }
     S.hist_used = out_base + n_out;
     S.lat_count += lat_new; S.lat_total += lat_new;
@@ -601,14 +617,14 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
 #endif
     if (abort_code != 0) S.status = abort_code;
   }
-  __syncthreads();
+  wg_sync<LDS>();
   PHASE_MARK(4);
   return true;
 }
 
 // One workgroup per lane.  is_init: (re)start the lane's channel and write frame 0.
 template <int NT>
-__global__ void __launch_bounds__(NT, 4) k_advance(DecDev D, const LaneParam *__restrict__ lanes, int is_init) {
+__global__ void __launch_bounds__(NT, NT / 128) k_advance(DecDev D, const LaneParam *__restrict__ lanes, int is_init) {
   __shared__ LaneShared<NT> S;
   const int tid = threadIdx.x;
   const LaneParam lp = lanes[blockIdx.x];
@@ -634,6 +650,8 @@ __global__ void __launch_bounds__(NT, 4) k_advance(DecDev D, const LaneParam *__
       S.lat_total = cs->lat_total; S.arcs_expanded = cs->arcs_expanded; S.max_pre = cs->max_pre;
       S.max_post = cs->max_post; S.iters_max = cs->closure_iters_max;
     }
+    S.in_off = 0; S.n_in = 0;
+    if (!is_init && S.nf >= 1 && S.nf <= D.max_frames + 1) { S.in_off = foff[S.nf - 1]; S.n_in = (int)(foff[S.nf] - foff[S.nf - 1]); }
 #ifdef WFST_PHASE_TIMING
     for (int k = 0; k < 16; ++k) S.ph[k] = 0;
     S.dbg_tok = 0; S.dbg_iters = 0; S.dbg_arcs = 0;
@@ -647,7 +665,7 @@ __global__ void __launch_bounds__(NT, 4) k_advance(DecDev D, const LaneParam *__
     const float *ll = is_init ? nullptr : lp.ll + (size_t)f * (size_t)lp.stride;
     const int nf = S.nf;
     bool small = is_init != 0;
-    if (!small && nf >= 1 && nf <= D.max_frames) small = (foff[nf] - foff[nf - 1]) <= (long long)LDS_NIN_MAX;
+    if (!small) small = S.n_in <= LDS_NIN_MAX;
     bool done = false;
     if (small) done = lane_frame<NT, true>(D, S, lp, ll, is_init != 0, slots, queue, aux, dkey, dslot, foff, hist, lat);
     if (!done) {
