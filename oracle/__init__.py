@@ -60,6 +60,8 @@ def lib():
         L.oracle_lattice.restype = i64
         L.oracle_best_path.argtypes = [vp, i32, vp, i32, vp, vp, i32, vp, vp, vp]
         L.oracle_best_path.restype = i32
+        L.oracle_final_lattice.argtypes = [vp, i32, vp, vp, vp, i64, vp, vp]
+        L.oracle_final_lattice.restype = i64
         L.oracle_closure.argtypes = [vp, i32, vp, vp, vp, i32, f32]
         L.oracle_closure.restype = i32
         _lib = L
@@ -152,6 +154,20 @@ class OracleDecoder:
         n = lib().oracle_lattice(self.h, from_frame, fr.ctypes.data, ar.ctypes.data, ex.ctypes.data, cap)
         assert n >= 0
         return fr[:n].copy(), ar[:n].copy(), ex[:n].copy()
+
+    def final_lattice(self, use_final: bool = True):
+        """Backward-pruned lattice: dict(frame, arc, extra sorted by (frame, arc), best_cost,
+        reached_final), or None if there is no token."""
+        cap = max(lib().oracle_num_lattice(self.h), 1)
+        fr, ar, ex = np.empty(cap, np.int32), np.empty(cap, np.uint32), np.empty(cap, np.float32)
+        bc, rf = C.c_float(), C.c_int32()
+        n = lib().oracle_final_lattice(self.h, int(use_final), fr.ctypes.data, ar.ctypes.data, ex.ctypes.data, cap,
+                                       C.byref(bc), C.byref(rf))
+        if n == -1:
+            return None
+        assert n >= 0
+        return dict(frame=fr[:n].copy(), arc=ar[:n].copy(), extra=ex[:n].copy(), best_cost=np.float32(bc.value),
+                    reached_final=bool(rf.value))
 
     def best_path(self, use_final: bool = True):
         """dict(words, arcs, total_cost, reached_final) or None if there is no token."""

@@ -37,7 +37,8 @@
 // parity unpinned: that these pruning rules select the same tokens as the paper's own
 // decoder cannot be checked (the paper prints no token sets, costs or lattices).
 // Everything else is pinned by tests/test_oracle_*.py (brute force over all paths,
-// shortest-path library routine, closed forms, sort-and-truncate, invariants).
+// shortest-path library routine, closed forms, sort-and-truncate, invariants; the final
+// lattice by brute force over all suffix paths).
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
@@ -320,6 +321,69 @@ int32_t oracle_best_path(const void *d, int32_t use_final, int32_t *words, int32
   }
   *n_words = nw; *n_arcs = (int32_t)path.size(); *total_cost = bc; *reached_final = rf;
   return 0;
+}
+
+// Final lattice: backward pruning of the recorded arcs with the lattice beam (the step the
+// paper leaves to the end of the utterance, Section 3.4).  Every token gets an extra cost
+//   te(n) = min over recorded arcs a: n -> m of (te(m) + extra(a)),
+// in the last frame te(n) = (cost(n) + final(n)) - best total (or cost(n) - best cost when no
+// final state holds a token, or use_final is 0; non-final tokens get +inf when finals are
+// used).  An arc a into m is kept iff te(m) + extra(a) <= lattice_beam.  All fp32, one
+// rounded add per step; the minimum makes the result independent of evaluation order.
+// Outputs the kept records sorted by (frame, arc); returns their number or -2 (cap).
+int64_t oracle_final_lattice(const void *d, int32_t use_final, int32_t *frame, uint32_t *arc, float *extra, int64_t cap,
+                             float *best_cost, int32_t *reached_final) {
+  const Decoder &D = *(const Decoder *)d; const Graph &g = *D.g;
+  const float INF = std::numeric_limits<float>::infinity();
+  if (D.frames.empty() || D.frames.back().empty()) return -1;
+  const int32_t T = (int32_t)D.frames.size() - 1;
+  std::vector<std::map<int32_t, float>> te(T + 1);
+  // last frame
+  bool any_final = false; float best = INF;
+  if (use_final)
+    for (auto &kv : D.frames[T]) if (g.fin[kv.first] != INF) { any_final = true; best = std::min(best, kv.second.cost + g.fin[kv.first]); }
+  if (!any_final) for (auto &kv : D.frames[T]) best = std::min(best, kv.second.cost);
+  for (auto &kv : D.frames[T]) {
+    float v;
+    if (any_final) v = g.fin[kv.first] != INF ? (kv.second.cost + g.fin[kv.first]) - best : INF;
+    else v = kv.second.cost - best;
+    te[T][kv.first] = v;
+  }
+  // records per frame
+  std::vector<std::vector<const LatRec *>> by_frame(T + 1);
+  for (auto &r : D.lat) if (r.frame >= 0 && r.frame <= T) by_frame[r.frame].push_back(&r);
+  for (int32_t f = T; f >= 0; --f) {
+    if (f < T) for (auto &kv : D.frames[f]) te[f][kv.first] = INF;
+    // arcs that leave frame f by an emitting arc land in frame f + 1
+    if (f < T)
+      for (const LatRec *r : by_frame[f + 1]) {
+        if (g.il[r->arc] == 0) continue;
+        float v = te[f + 1][g.dst[r->arc]] + r->extra;
+        float &t = te[f][g.src[r->arc]];
+        if (v < t) t = v;
+      }
+    // non-emitting arcs stay inside frame f: relax until nothing changes
+    for (bool changed = true; changed;) {
+      changed = false;
+      for (const LatRec *r : by_frame[f]) {
+        if (g.il[r->arc] != 0) continue;
+        float v = te[f][g.dst[r->arc]] + r->extra;
+        float &t = te[f][g.src[r->arc]];
+        if (v < t) { t = v; changed = true; }
+      }
+    }
+  }
+  std::vector<LatRec> kept;
+  for (auto &r : D.lat) {
+    if (r.frame < 0 || r.frame > T) continue;
+    float v = te[r.frame][g.dst[r.arc]] + r.extra;
+    if (v <= D.lbeam) kept.push_back(r);
+  }
+  std::sort(kept.begin(), kept.end(), [](const LatRec &a, const LatRec &b) { return a.frame != b.frame ? a.frame < b.frame : a.arc < b.arc; });
+  if ((int64_t)kept.size() > cap) return -2;
+  for (size_t i = 0; i < kept.size(); ++i) { frame[i] = kept[i].frame; arc[i] = kept[i].arc; extra[i] = kept[i].extra; }
+  *best_cost = best; *reached_final = any_final ? 1 : 0;
+  return (int64_t)kept.size();
 }
 
 // Stand-alone closure of a token set (for tests): in/out arrays of (state, cost, in_arc as

@@ -397,3 +397,82 @@ def test_arcs_expanded_is_the_sum_of_out_degrees():
         st, _, _ = d.tokens(t)
         total += n_eps[st].sum() + (n_emit[st].sum() if t < T else 0)
     assert d.arcs_expanded == total
+
+
+# ---- final lattice (Section 3.4: the lattice generated at the end of the utterance) ----------
+
+def _final_lattice_by_enumeration(g, d, T, lbeam, use_final):
+    """Every recorded arc is kept iff some path of recorded arcs from its destination to the last
+    frame, folded from the end in fp32 (v = F32(v + extra) per arc), stays within the lattice
+    beam.  All suffix paths are enumerated explicitly."""
+    src = arc_sources(g)
+    fr, ar, ex = d.lattice()
+    out = {}
+    for f, a, e in zip(fr.tolist(), ar.tolist(), ex):
+        node = (f - (1 if g.ilabel[a] != 0 else 0), int(src[a]))
+        out.setdefault(node, []).append(((f, int(g.nextstate[a])), F32(e)))
+    st, co, _ = d.tokens(T)
+    fin = {int(s): F32(c) + F32(g.final_cost[s]) for s, c in zip(st, co) if np.isfinite(g.final_cost[s])} if use_final else {}
+    if fin:
+        best = min(fin.values())
+        end = {(T, s): F32(v - best) for s, v in fin.items()}
+    else:
+        best = min(F32(c) for c in co)
+        end = {(T, int(s)): F32(F32(c) - best) for s, c in zip(st, co)}
+
+    def suffix_values(node):
+        """fp32 right-fold values of all paths from node to an end node."""
+        vals = [end[node]] if node in end else []
+        for nxt, e in out.get(node, []):
+            if nxt[0] == T and nxt not in end and nxt not in out:
+                continue
+            vals += [F32(v + e) for v in suffix_values(nxt)]
+        return vals
+
+    kept = []
+    for f, a, e in zip(fr.tolist(), ar.tolist(), ex):
+        vals = suffix_values((f, int(g.nextstate[a])))
+        if vals and F32(min(vals) + F32(e)) <= lbeam:
+            kept.append((f, a))
+    return sorted(kept), best
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_final_lattice_equals_enumeration_of_suffix_paths(seed):
+    rng = np.random.default_rng(700 + seed)
+    integer = bool(seed % 2)
+    g = random_graph(rng, num_states=14, n_emit_per_state=(1, 3), eps_prob=0.06, num_pdfs=4, wmax=3,
+                     integer=integer, n_final=4)
+    T = 6
+    ll = (-rng.integers(0, 3, size=(T, 4)).astype(F32)) if integer else rng.normal(-3, 1.5, size=(T, 4)).astype(F32)
+    lbeam = 2.5
+    d = decode(g, ll, beam=5.0, lattice_beam=lbeam, alpha=6)
+    for use_final in (True, False):
+        want, best = _final_lattice_by_enumeration(g, d, T, lbeam, use_final)
+        got = d.final_lattice(use_final)
+        assert sorted(zip(got["frame"].tolist(), got["arc"].tolist())) == want
+        assert got["best_cost"] == best
+
+
+def test_final_lattice_invariants():
+    rng = np.random.default_rng(8)
+    g = random_graph(rng, num_states=60, n_emit_per_state=(2, 4), eps_prob=0.03, num_pdfs=8, n_final=12)
+    T = 30
+    ll = rng.normal(-4, 2, size=(T, 8)).astype(F32)
+    sizes = []
+    for lbeam in (0.0, 1.0, 4.0):
+        d = decode(g, ll, beam=8.0, lattice_beam=lbeam, alpha=25)
+        fl = d.final_lattice(True)
+        kept = set(zip(fl["frame"].tolist(), fl["arc"].tolist()))
+        raw = set(zip(*[x.tolist() for x in d.lattice()[:2]]))
+        assert kept <= raw
+        bp = d.best_path(True)
+        assert fl["best_cost"] == bp["total_cost"] and fl["reached_final"] == bp["reached_final"]
+        # every arc of the best path survives, in its frame
+        f = 0
+        for a in bp["arcs"]:
+            if g.ilabel[a] != 0:
+                f += 1
+            assert (f, int(a)) in kept
+        sizes.append(len(kept))
+    assert sizes[0] <= sizes[1] <= sizes[2]
