@@ -189,6 +189,27 @@ int wfst_decode_lattice_arcs_batch(wfst_decoder_t *decoder, const int32_t *chann
                                    wfst_lat_arc_t *out, int64_t cap, int64_t *offsets,
                                    int32_t out_is_device);
 
+/* Final lattice of a channel (the step the paper leaves to the end of the utterance, Section
+ * 3.4): backward pruning, with the lattice beam, of the lattice arcs currently buffered for
+ * the channel (all arcs since its last drain; nothing is drained).  Every token gets an extra
+ * cost te = min over buffered arcs leaving it of (te of the arc's destination + the arc's
+ * extra cost); in the last frame te is the token's cost (+ final cost, over final states, if
+ * use_final and one holds a token) minus the best such cost.  An arc is kept iff te of its
+ * destination + its extra cost <= lattice_beam.  The kept arcs are copied to `out` (HOST or
+ * DEVICE as flagged) in no particular order; WFST_E_CAPACITY with *n = needed if cap is too
+ * small.  info->density = kept arcs per frame.  Synchronises; allocates scratch. */
+typedef struct {
+  int64_t arcs_in;        /* buffered arcs examined                        */
+  int64_t arcs_kept;
+  int32_t frames;         /* token frames of the channel                   */
+  int32_t reached_final;
+  float best_cost;        /* cost of the best path the pruning is based on */
+  float density;          /* arcs_kept / max(frames - 1, 1)                */
+} wfst_lattice_info_t;
+int wfst_decode_final_lattice(wfst_decoder_t *decoder, int32_t channel, int32_t use_final,
+                              wfst_lat_arc_t *out, int64_t cap, int64_t *n, int32_t out_is_device,
+                              wfst_lattice_info_t *info);
+
 /* Tokens kept for one frame of a channel (frame -1 = last), in no particular order.
  * out: HOST [cap].  A parity hook: the token history is what best_path walks. */
 int wfst_decode_tokens(wfst_decoder_t *decoder, int32_t channel, int32_t frame,

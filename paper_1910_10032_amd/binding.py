@@ -24,7 +24,7 @@ EXPORTS = [
     "wfst_decode_graph_load", "wfst_decode_graph_free", "wfst_decode_graph_bytes", "wfst_decode_create",
     "wfst_decode_destroy", "wfst_decode_state_bytes", "wfst_decode_init_channels", "wfst_decode_free_channels",
     "wfst_decode_advance", "wfst_decode_best_path_batch", "wfst_decode_best_path", "wfst_decode_best_path_arcs",
-    "wfst_decode_lattice_arcs", "wfst_decode_lattice_arcs_batch", "wfst_decode_tokens", "wfst_decode_stats", "wfst_decode_set_profiling",
+    "wfst_decode_lattice_arcs", "wfst_decode_lattice_arcs_batch", "wfst_decode_final_lattice", "wfst_decode_tokens", "wfst_decode_stats", "wfst_decode_set_profiling",
     "wfst_decode_profile", "wfst_decode_strerror",
 ]
 
@@ -47,6 +47,11 @@ class wfst_stats_t(C.Structure):
     _fields_ = [("frames", C.c_int64), ("arcs_expanded", C.c_int64), ("lattice_arcs", C.c_int64),
                 ("tokens", C.c_int64), ("max_tokens_pre_prune", C.c_int32), ("max_tokens", C.c_int32),
                 ("closure_iters_max", C.c_int32), ("status", C.c_int32)]
+
+
+class wfst_lattice_info_t(C.Structure):
+    _fields_ = [("arcs_in", C.c_int64), ("arcs_kept", C.c_int64), ("frames", C.c_int32),
+                ("reached_final", C.c_int32), ("best_cost", C.c_float), ("density", C.c_float)]
 
 
 LAT_DTYPE = np.dtype([("frame", np.int32), ("arc", np.uint32), ("extra_cost", np.float32)])
@@ -80,6 +85,7 @@ def lib():
         L.wfst_decode_best_path_arcs.argtypes = [vp, i32, i32, vp, i32, C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(i32)]
         L.wfst_decode_lattice_arcs.argtypes = [vp, i32, i32, vp, i64, C.POINTER(i64), i32]
         L.wfst_decode_lattice_arcs_batch.argtypes = [vp, vp, i32, vp, i64, vp, i32]
+        L.wfst_decode_final_lattice.argtypes = [vp, i32, i32, vp, i64, C.POINTER(i64), i32, C.POINTER(wfst_lattice_info_t)]
         L.wfst_decode_tokens.argtypes = [vp, i32, i32, vp, i32, C.POINTER(i32)]
         L.wfst_decode_stats.argtypes = [vp, i32, C.POINTER(wfst_stats_t)]
         L.wfst_decode_set_profiling.argtypes = [vp, i32]
@@ -283,6 +289,19 @@ class WfstDecoder:
                 continue
             _check(rc, "wfst_decode_lattice_arcs_batch")
             return out[:offs[-1]].copy(), offs
+
+    def final_lattice(self, channel: int, use_final: bool = True, cap: int = 1 << 16):
+        """(kept arcs as a structured array, info dict) of wfst_decode_final_lattice."""
+        while True:
+            out = np.zeros(max(cap, 1), LAT_DTYPE)
+            n, info = C.c_int64(), wfst_lattice_info_t()
+            rc = lib().wfst_decode_final_lattice(self.h, channel, int(use_final), out.ctypes.data, cap, C.byref(n), 0,
+                                                 C.byref(info))
+            if rc == WFST_E_CAPACITY:
+                cap = n.value
+                continue
+            _check(rc, "wfst_decode_final_lattice")
+            return out[:n.value].copy(), {k: getattr(info, k) for k, _ in wfst_lattice_info_t._fields_}
 
     def tokens(self, channel: int, frame: int = -1, cap: int = 1 << 14):
         while True:

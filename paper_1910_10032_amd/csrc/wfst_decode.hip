@@ -50,6 +50,7 @@ struct wfst_decoder {
   std::vector<int32_t> staged_chans;    // what d_chans currently holds
   PathOut *d_pathout = nullptr;
   void *d_stage = nullptr; size_t stage_bytes = 0;
+  void *d_stage2 = nullptr; size_t stage2_bytes = 0;   // scratch of the final-lattice pass
   unsigned long long *d_cnt = nullptr;
   long long *d_offs = nullptr;          // readout scratch [max(num_channels, max_lanes) + 1]
   bool profiling = false;
@@ -296,6 +297,7 @@ void wfst_decode_destroy(wfst_decoder_t *d) {
   (void)hipDeviceSynchronize();
   for (void *p : d->allocs) (void)hipFree(p);
   if (d->d_stage) (void)hipFree(d->d_stage);
+  if (d->d_stage2) (void)hipFree(d->d_stage2);
   for (int i = 0; i < PARAM_RING; ++i) {
     if (d->h_params[i]) (void)hipHostFree(d->h_params[i]);
     if (d->param_ev[i]) (void)hipEventDestroy(d->param_ev[i]);
@@ -512,6 +514,49 @@ int wfst_decode_lattice_arcs_batch(wfst_decoder_t *d, const int32_t *channels, i
   hipLaunchKernelGGL(k_reset_lattice_batch, dim3((n + 255) / 256), dim3(256), 0, 0, d->dev, (const int32_t *)d->d_chans, n);
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipDeviceSynchronize());
+  return 0;
+}
+
+int wfst_decode_final_lattice(wfst_decoder_t *d, int32_t channel, int32_t use_final, wfst_lat_arc_t *out, int64_t cap,
+                              int64_t *n, int32_t out_is_device, wfst_lattice_info_t *info) {
+  if (!d || !n || !info || cap < 0 || (cap > 0 && !out)) return WFST_E_INVALID_ARG;
+  int rc = check_channels(d, &channel, 1, true);
+  if (rc) return rc;
+  ChanState cs;
+  rc = read_chan(d, channel, &cs);
+  if (rc) return rc;
+  if (cs.status != 0) return cs.status;
+  // scratch: one word per kept token, one offset per frame, the info block
+  const size_t te_bytes = sizeof(uint32_t) * (size_t)std::max<long long>(cs.hist_used, 1);
+  const size_t rs_off = (te_bytes + 15) & ~(size_t)15;
+  const size_t info_off = rs_off + sizeof(long long) * ((size_t)cs.num_frames + 3);
+  const size_t need = info_off + sizeof(LatticeInfoDev);
+  if (need > d->stage2_bytes) {
+    if (d->d_stage2) HIP_TRY(hipFree(d->d_stage2));
+    d->d_stage2 = nullptr; d->stage2_bytes = 0;
+    HIP_TRY(hipMalloc(&d->d_stage2, need));
+    d->stage2_bytes = need;
+  }
+  LatRec *dst = (LatRec *)out;
+  if (!out_is_device) {
+    rc = ensure_stage(d, sizeof(LatRec) * (size_t)std::max<int64_t>(cap, 1));
+    if (rc) return rc;
+    dst = (LatRec *)d->d_stage;
+  }
+  char *base = (char *)d->d_stage2;
+  hipLaunchKernelGGL(k_final_lattice, dim3(1), dim3(1024), 0, 0, d->dev, channel, use_final, (uint32_t *)base,
+                     (long long *)(base + rs_off), dst, (long long)cap, (LatticeInfoDev *)(base + info_off));
+  HIP_TRY(hipGetLastError());
+  LatticeInfoDev li;
+  HIP_TRY(hipMemcpy(&li, base + info_off, sizeof(li), hipMemcpyDeviceToHost));
+  if (li.status == WFST_E_CAPACITY) { *n = li.arcs_kept; return WFST_E_CAPACITY; }
+  if (li.status != 0) return li.status;
+  if (!out_is_device && li.arcs_kept > 0)
+    HIP_TRY(hipMemcpy(out, dst, sizeof(LatRec) * (size_t)li.arcs_kept, hipMemcpyDeviceToHost));
+  *n = li.arcs_kept;
+  info->arcs_in = li.arcs_in; info->arcs_kept = li.arcs_kept; info->frames = li.frames;
+  info->reached_final = li.reached_final; info->best_cost = li.best_cost;
+  info->density = (float)((double)li.arcs_kept / (double)std::max(li.frames - 1, 1));
   return 0;
 }
 

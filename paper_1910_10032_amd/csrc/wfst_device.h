@@ -63,7 +63,10 @@ struct __align__(16) HTok {  // one kept token of one frame
 };
 constexpr uint32_t PREV_SAME = 0x80000000u;
 
-struct LatRec { int32_t frame; uint32_t arc; float extra; };
+struct LatRec { int32_t frame; uint32_t arc; float extra; };   // as handed to the caller
+// As buffered on the device: also the kept-token indices of both ends, for the final lattice.
+// dst: index in frame `frame`; src: index in frame `frame` - 1, or in `frame` if PREV_SAME is set.
+struct LatInt { int32_t frame; uint32_t arc; float extra; uint32_t dst; uint32_t src; };
 
 struct ChanState {
   int32_t status;            // sticky error code (WFST_E_*) or 0
@@ -86,7 +89,7 @@ struct DecDev {
   ChanState *chan;
   long long *frame_off;      // [num_channels][max_frames + 2] start of each frame in hist
   HTok *hist;                // [num_channels][hist_cap]
-  LatRec *lat;               // [num_channels][lat_cap]
+  LatInt *lat;               // [num_channels][lat_cap]
   Slot *slots;               // [max_lanes][H]
   uint32_t *queue;           // [max_lanes][qcap]
   Aux *aux;                  // [max_lanes][auxcap]

@@ -233,7 +233,7 @@ __device__ void block_select(LaneShared<NT> &S, int n, uint32_t need, uint32_t l
 template <int NT, bool LDS>
 __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &lp, const float *ll, bool is_init,
                            Slot *gslots, uint32_t *queue, Aux *aux, uint32_t *dkey, uint32_t *dslot,
-                           long long *foff, HTok *hist, LatRec *lat) {
+                           long long *foff, HTok *hist, LatInt *lat) {
   const int tid = threadIdx.x;
   const uint32_t *rec = D.g.rec;
   Slot *slots = LDS ? S.table : gslots;
@@ -537,10 +537,10 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
   if (abort_code == 0) {
     const long long lat_base = S.lat_count;
     const uint32_t n_aux = min(S.auxn, (uint32_t)D.auxcap);
-    auto emit_lat = [&](uint32_t arc, float extra) {
+    auto emit_lat = [&](uint32_t arc, float extra, uint32_t dst, uint32_t src) {
       const uint32_t p = wave_alloc(&S.latn);
       if (lat_base + (long long)p >= D.lat_cap) atomicOr(&S.flags, F_LATOVF);
-      else lat[lat_base + p] = LatRec{nf, arc, extra};
+      else lat[lat_base + p] = LatInt{nf, arc, extra, dst, src};
     };
     for (uint32_t i0 = 0; i0 < n_aux; i0 += NT * LAT_U) {
       Aux a[LAT_U];
@@ -561,7 +561,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
           if (pack(okey(a[u].x), a[u].arc) == v) hist[out_base + pos].prev = a[u].src;
           if (D.lattice_on && a[u].x <= cutoff_eff) {
             const float extra = a[u].x - key2f((uint32_t)(v >> 32));
-            if (extra <= D.lattice_beam) emit_lat(a[u].arc, extra);
+            if (extra <= D.lattice_beam) emit_lat(a[u].arc, extra, pos, a[u].src);
           }
         } else {
           // epsilon arc {slot of the source | AUX_EPS, weight, arc, handle of the destination}
@@ -579,7 +579,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
           if (pack(okey(x), a[u].arc) == v) hist[out_base + pos].prev = spos | PREV_SAME;
           if (D.lattice_on) {
             const float extra = x - key2f((uint32_t)(v >> 32));
-            if (extra <= D.lattice_beam) emit_lat(a[u].arc, extra);
+            if (extra <= D.lattice_beam) emit_lat(a[u].arc, extra, pos, spos | PREV_SAME);
           }
         }
       }
@@ -636,7 +636,7 @@ __global__ void __launch_bounds__(NT, NT / 128) k_advance(DecDev D, const LanePa
   uint32_t *dslot = D.dslot + (size_t)blockIdx.x * (size_t)D.tokcap;
   long long *foff = D.frame_off + (size_t)lp.chan * (size_t)(D.max_frames + 2);
   HTok *hist = D.hist + (size_t)lp.chan * (size_t)D.hist_cap;
-  LatRec *lat = D.lat + (size_t)lp.chan * (size_t)D.lat_cap;
+  LatInt *lat = D.lat + (size_t)lp.chan * (size_t)D.lat_cap;
 
   const Slot fresh{~0ull, EMPTY, A_FRESH};
   for (int i = tid; i < LDS_SLOTS; i += NT) S.table[i] = fresh;
@@ -869,9 +869,9 @@ __global__ void k_export_tokens(DecDev D, int ch, long long off, int n, TokOut *
 // the running output count (zeroed by the host).
 __global__ void k_export_lattice(DecDev D, int ch, long long n, int from_frame, LatRec *out, long long cap,
                                  unsigned long long *cnt) {
-  const LatRec *lat = D.lat + (size_t)ch * (size_t)D.lat_cap;
+  const LatInt *lat = D.lat + (size_t)ch * (size_t)D.lat_cap;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) {
-    const LatRec r = lat[i];
+    const LatInt r = lat[i];
     if (r.frame < from_frame) continue;
     const unsigned long long p = atomicAdd(cnt, 1ull);
     if ((long long)p < cap) out[p] = LatRec{r.frame, D.g.orig[r.arc], r.extra};
@@ -913,16 +913,126 @@ __global__ void __launch_bounds__(1024) k_lattice_offsets(DecDev D, const int32_
 }
 __global__ void k_export_lattice_batch(DecDev D, const int32_t *chans, const long long *offs, LatRec *out) {
   const int ch = chans[blockIdx.x];
-  const LatRec *lat = D.lat + (size_t)ch * (size_t)D.lat_cap;
+  const LatInt *lat = D.lat + (size_t)ch * (size_t)D.lat_cap;
   const long long o = offs[blockIdx.x], n = offs[blockIdx.x + 1] - o;
   for (long long i = (long long)blockIdx.y * blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.y * blockDim.x) {
-    const LatRec r = lat[i];
+    const LatInt r = lat[i];
     out[o + i] = LatRec{r.frame, D.g.orig[r.arc], r.extra};
   }
 }
 __global__ void k_reset_lattice_batch(DecDev D, const int32_t *chans, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) D.chan[chans[i]].lat_count = 0;
+}
+
+// ---- final lattice -------------------------------------------------------------------------
+// Backward pruning of a channel's buffered lattice arcs with the lattice beam (the paper's
+// Section 3.4 leaves this to the end of the utterance).  te(n), the extra cost of token n, is
+// the minimum over recorded arcs a: n -> m of te(m) + extra(a); in the last frame it is the
+// token's distance to the best (final) cost.  An arc into m is kept iff te(m) + extra(a) <=
+// lattice_beam.  fp32, one rounded add per step; minima via integer atomics on the (non-
+// negative) float bits, so the result does not depend on thread order.  One workgroup.
+struct LatticeInfoDev { long long arcs_in, arcs_kept; int32_t frames, reached_final, status, pad; float best_cost, pad2; };
+
+__global__ void __launch_bounds__(1024) k_final_lattice(DecDev D, int ch, int use_final, uint32_t *te, long long *rec_start,
+                                                        LatRec *out, long long cap, LatticeInfoDev *info) {
+  const int tid = threadIdx.x, NTH = 1024;
+  const ChanState *cs = D.chan + ch;
+  const long long *foff = D.frame_off + (size_t)ch * (size_t)(D.max_frames + 2);
+  const HTok *hist = D.hist + (size_t)ch * (size_t)D.hist_cap;
+  const LatInt *lat = D.lat + (size_t)ch * (size_t)D.lat_cap;
+  const uint32_t *rec = D.g.rec;
+  __shared__ uint32_t s_best_f, s_best_n, s_changed;
+  __shared__ unsigned long long s_kept;
+  const int st = cs->status;
+  const bool readable = st == 0;
+  const int T = cs->num_frames - 1;
+  const long long n_rec = cs->lat_count;
+  const long long n_tok = cs->hist_used;
+  const long long oT = T >= 0 ? foff[T] : 0;
+  const int nT = T >= 0 ? (int)(foff[T + 1] - oT) : 0;
+  if (!readable || nT == 0) {
+    if (tid == 0) { LatticeInfoDev li{n_rec, 0, T + 1, 0, readable ? E_DEAD_CHANNEL : st, 0, 0.f, 0.f}; *info = li; }
+    return;
+  }
+  if (tid == 0) { s_best_f = KEY_NONE; s_best_n = KEY_NONE; s_kept = 0; }
+  for (long long i = tid; i < n_tok; i += NTH) te[i] = 0x7F800000u;            // +inf
+  for (int f = tid; f <= T + 2; f += NTH) rec_start[f] = f > T ? n_rec : -1;
+  __syncthreads();
+  // start of each frame's run of records (records are appended frame by frame)
+  for (long long i = tid; i < n_rec; i += NTH) {
+    const int f = lat[i].frame;
+    if (i == 0 || lat[i - 1].frame != f) rec_start[f] = i;
+  }
+  // best cost over the last frame
+  for (int i = tid; i < nT; i += NTH) {
+    const HTok t = hist[oT + i];
+    atomicMin(&s_best_n, okey(t.cost));
+    if (use_final) {
+      const float fc = __uint_as_float(rec[3 * (size_t)(t.handle & HMASK) + 2]);
+      if (fc != INFINITY) atomicMin(&s_best_f, okey(t.cost + fc));
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {                                   // frames without records inherit the next start
+    long long nxt = n_rec;
+    for (int f = T; f >= 0; --f) { if (rec_start[f] < 0) rec_start[f] = nxt; else nxt = rec_start[f]; }
+  }
+  const bool any_final = use_final && s_best_f != KEY_NONE;
+  const float best = key2f(any_final ? s_best_f : s_best_n);
+  for (int i = tid; i < nT; i += NTH) {
+    const HTok t = hist[oT + i];
+    float v;
+    if (any_final) {
+      const float fc = __uint_as_float(rec[3 * (size_t)(t.handle & HMASK) + 2]);
+      v = fc != INFINITY ? (t.cost + fc) - best : INFINITY;
+    } else {
+      v = t.cost - best;
+    }
+    te[oT + i] = __float_as_uint(v);
+  }
+  __syncthreads();
+  for (int f = T; f >= 0; --f) {
+    const long long of = foff[f];
+    if (f < T) {                                    // emitting arcs recorded with frame f + 1 start in frame f
+      const long long of1 = foff[f + 1];
+      for (long long i = rec_start[f + 1] + tid; i < rec_start[f + 2]; i += NTH) {
+        const LatInt r = lat[i];
+        if (r.src & PREV_SAME) continue;
+        const float v = __uint_as_float(ld32(&te[of1 + r.dst])) + r.extra;
+        atomicMin(&te[of + r.src], __float_as_uint(v));
+      }
+      __syncthreads();
+    }
+    const long long e0 = rec_start[f], e1 = rec_start[f + 1];
+    for (;;) {                                      // epsilon arcs inside frame f, to the fixed point
+      if (tid == 0) s_changed = 0;
+      __syncthreads();
+      for (long long i = e0 + tid; i < e1; i += NTH) {
+        const LatInt r = lat[i];
+        if (!(r.src & PREV_SAME)) continue;
+        const uint32_t v = __float_as_uint(__uint_as_float(ld32(&te[of + r.dst])) + r.extra);
+        if (v < atomicMin(&te[of + (r.src & ~PREV_SAME)], v)) s_changed = 1;
+      }
+      __syncthreads();
+      if (!s_changed) break;
+      __syncthreads();
+    }
+  }
+  for (long long i = tid; i < n_rec; i += NTH) {
+    const LatInt r = lat[i];
+    const float v = __uint_as_float(ld32(&te[foff[r.frame] + r.dst])) + r.extra;
+    if (v <= D.lattice_beam) {
+      const unsigned long long p = atomicAdd(&s_kept, 1ull);
+      if ((long long)p < cap) out[p] = LatRec{r.frame, D.g.orig[r.arc], r.extra};
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    LatticeInfoDev li{n_rec, (long long)s_kept, T + 1, any_final ? 1 : 0, 0, 0, best, 0.f};
+    if ((long long)s_kept > cap) li.status = E_CAPACITY;
+    *info = li;
+  }
 }
 
 }  // namespace wfst

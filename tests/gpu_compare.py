@@ -27,6 +27,8 @@ def compare_channel(dec, ch, od, frames=None, lattice=True, label=""):
         assert np.array_equal(gs, os_), f"{label} frame {f}: token states differ ({len(gs)} vs {len(os_)})"
         assert np.array_equal(gc.view(np.uint32), oc.view(np.uint32)), f"{label} frame {f}: costs differ"
         assert np.array_equal(ga, oa), f"{label} frame {f}: best incoming arcs differ"
+    if lattice and od.status == 0:
+        check_final_lattice(dec, ch, od, label)
     if lattice:
         lat = dec.lattice_arcs(ch)
         o = np.lexsort((lat["arc"], lat["frame"]))
@@ -44,3 +46,18 @@ def compare_channel(dec, ch, od, frames=None, lattice=True, label=""):
             assert g["reached_final"] == bp["reached_final"], label
             ga = dec.best_path_arcs(ch, use_final)
             assert np.array_equal(ga["arcs"].astype(np.int64), bp["arcs"]), f"{label} best-path arcs differ"
+
+
+def check_final_lattice(dec, ch, od, label=""):
+    """Backward-pruned lattice of the arcs still buffered on the device (nothing drained yet)
+    against the checker's, for both kinds of end condition."""
+    for use_final in (True, False):
+        got, info = dec.final_lattice(ch, use_final)
+        want = od.final_lattice(use_final)
+        o = np.lexsort((got["arc"], got["frame"]))
+        assert len(got) == len(want["frame"]) == info["arcs_kept"], f"{label} final lattice size {len(got)} != {len(want['frame'])}"
+        assert np.array_equal(got["frame"][o], want["frame"]) and np.array_equal(got["arc"][o], want["arc"]), f"{label} final lattice arcs"
+        assert np.array_equal(got["extra_cost"][o].view(np.uint32), want["extra"].view(np.uint32)), label
+        assert np.float32(info["best_cost"]).view(np.uint32) == np.float32(want["best_cost"]).view(np.uint32), label
+        assert bool(info["reached_final"]) == want["reached_final"], label
+        assert info["frames"] == od.num_frames

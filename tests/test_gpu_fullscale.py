@@ -8,7 +8,7 @@ import pytest
 
 import oracle
 import synth
-from gpu_compare import sorted_tokens
+from gpu_compare import check_final_lattice, sorted_tokens
 
 pytestmark = pytest.mark.gpu
 
@@ -46,8 +46,10 @@ def decode_and_compare(cfg, sample, token_capacity, history_capacity, lattice_ca
             recs, offs = dec.lattice_arcs_batch(chans)
             for s in sample:
                 lat[s].append(recs[offs[s]:offs[s + 1]])
+    final_checks = []
     if not cfg.chunk:                                  # offline: one readout per sampled channel at the end
         for s in sample:
+            final_checks.append((s, dec.final_lattice(s, True), dec.final_lattice(s, False)))
             lat[s].append(dec.lattice_arcs(s))
     torch.cuda.synchronize()
     statuses = [dec.stats(int(c))["status"] for c in chans]
@@ -73,6 +75,16 @@ def decode_and_compare(cfg, sample, token_capacity, history_capacity, lattice_ca
         assert len(got) == len(fr) == st["lattice_arcs"], label
         assert np.array_equal(got["frame"][o], fr) and np.array_equal(got["arc"][o], ar), label
         assert np.array_equal(got["extra_cost"][o].view(np.uint32), ex.view(np.uint32)), label
+        for (cs_, with_final, without_final) in final_checks:
+            if cs_ != s:
+                continue
+            for use_final, (got, info) in ((True, with_final), (False, without_final)):
+                want = od.final_lattice(use_final)
+                o2 = np.lexsort((got["arc"], got["frame"]))
+                assert len(got) == len(want["frame"]), f"{label} final lattice size"
+                assert np.array_equal(got["frame"][o2], want["frame"]) and np.array_equal(got["arc"][o2], want["arc"]), label
+                assert np.array_equal(got["extra_cost"][o2].view(np.uint32), want["extra"].view(np.uint32)), label
+                assert np.float32(info["best_cost"]).view(np.uint32) == np.float32(want["best_cost"]).view(np.uint32), label
         for use_final in (True, False):
             bp, gp = od.best_path(use_final), dec.best_path(s, use_final)
             assert np.array_equal(gp["words"], bp["words"]), label
