@@ -41,6 +41,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-readout", action="store_true", help="time the advance calls only")
     ap.add_argument("--cpu-streams", type=int, default=12)
+    ap.add_argument("--groups", type=int, default=1, help="decoder groups the channels are split into (staggered)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 1 GiB device copy (calibrates the HBM byte counters under rocprofv3)")
     args = ap.parse_args()
@@ -75,51 +76,83 @@ def main() -> int:
     P = cfg.graph.num_pdfs
 
     t_setup = time.perf_counter()
+    G = max(1, min(args.groups, n_ch))
     g = synth.make_graph(cfg.graph)
     graph = B.WfstGraph(g)
-    dec = B.WfstDecoder(graph, cfg.beam, cfg.lattice_beam, cfg.max_active, num_channels=n_ch, max_lanes=n_ch,
-                        max_frames=n_frames, token_capacity=16384, history_capacity=2_500_000,
-                        lattice_capacity=400_000)
+    # The channels are split into G groups, each with its own decoder and stream.  The groups
+    # run staggered: while the host reads out one group's chunk, the others are decoding, so
+    # the per-chunk readouts do not stall the GPU (the paper's second-stream idea, Section 3).
+    bounds = [n_ch * k // G for k in range(G + 1)]
     scores = torch.empty((n_ch, n_frames, P), dtype=torch.float32, device="cuda")
     for s in range(n_ch):
         synth.device_loglikes(scores[s], cfg.ll_seed, s, 0, cfg.ll_mu, cfg.ll_sigma, cfg.ll_boost)
     torch.cuda.synchronize()
+    groups = []
+    for k in range(G):
+        lo, hi = bounds[k], bounds[k + 1]
+        n = hi - lo
+        dec = B.WfstDecoder(graph, cfg.beam, cfg.lattice_beam, cfg.max_active, num_channels=n, max_lanes=n,
+                            max_frames=n_frames, token_capacity=16384, history_capacity=2_500_000,
+                            lattice_capacity=400_000)
+        ch_np = np.arange(n, dtype=np.int32)
+        dec.init_channels(ch_np)
+        groups.append(dict(dec=dec, ch=ch_np, n=n, stream=torch.cuda.Stream().cuda_stream,
+                           strides=np.full(n, P, np.int32), nfr=np.full(n, chunk, np.int32),
+                           row0=scores.data_ptr() + np.arange(lo, hi, dtype=np.uint64) * np.uint64(n_frames * P * 4),
+                           lat_buf=torch.empty(n * 80_000 * 12, dtype=torch.uint8, device="cuda")))
     chans = list(range(n_ch))
-    dec.init_channels(chans)
-    lat_buf = torch.empty(n_ch * 80_000 * 12, dtype=torch.uint8, device="cuda")
-    stream = torch.cuda.current_stream().cuda_stream
-
-    ch_np = np.arange(n_ch, dtype=np.int32)
-    strides_np = np.full(n_ch, P, np.int32)
-    nfr_np = np.full(n_ch, chunk, np.int32)
-    row0 = scores.data_ptr() + np.arange(n_ch, dtype=np.uint64) * np.uint64(n_frames * P * 4)
-
-    def step(i: int, readout: bool):
-        ptrs = row0 + np.uint64(i * chunk * P * 4)
-        dec.advance_ptrs(ch_np, ptrs, strides_np, nfr_np, stream)
-        if readout:
-            paths = dec.best_path_batch(ch_np, use_final=False, words_cap=1024, raw=True)
-            offs = dec.lattice_arcs_batch(ch_np, out_device=lat_buf)
-            return paths, offs
-        return None
-
     readout = not args.no_readout
-    for i in range(W):
-        step(i, readout)
-    torch.cuda.synchronize()
-    stats0 = [dec.stats(c) for c in chans]
+
+    def launch(gr, i: int):
+        gr["dec"].advance_ptrs(gr["ch"], gr["row0"] + np.uint64(i * chunk * P * 4), gr["strides"], gr["nfr"], gr["stream"])
+
+    def read(gr):
+        if not readout:
+            return None
+        paths = gr["dec"].best_path_batch(gr["ch"], use_final=False, words_cap=1024, raw=True)
+        offs = gr["dec"].lattice_arcs_batch(gr["ch"], out_device=gr["lat_buf"])
+        return paths, offs
+
+    def all_stats():
+        return [gr["dec"].stats(int(c)) for gr in groups for c in gr["ch"]]
+
+    def run(first: int, count: int, offset_s: float = 0.0):
+        """Steps [first, first + count): every group advances one chunk per step and is read out.
+        offset_s spaces the groups' first launches so that their chunks complete at different
+        times (the delay is inside the timed region)."""
+        last = [None] * G
+        for k, gr in enumerate(groups):
+            if k and offset_s > 0:
+                time.sleep(offset_s)
+            launch(gr, first)
+        for i in range(first, first + count):
+            for k, gr in enumerate(groups):
+                last[k] = read(gr)                 # waits for this group's chunk i only
+                if i + 1 < first + count:
+                    launch(gr, i + 1)              # its next chunk decodes while the other groups are read
+        torch.cuda.synchronize()
+        return last
+
+    offset_s = 0.0
+    if W:
+        tw = time.perf_counter()
+        run(0, W)
+        offset_s = (time.perf_counter() - tw) / W / G if G > 1 else 0.0
+    stats0 = all_stats()
     arcs0 = sum(s["arcs_expanded"] for s in stats0)
-    dec.set_profiling(True)
+    for gr in groups:
+        gr["dec"].set_profiling(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    last = None
-    for i in range(W, W + K):
-        last = step(i, readout)
-    torch.cuda.synchronize()
+    last = run(W, K, offset_s)
     t1 = time.perf_counter()
-    launches, kernel_ms = dec.profile()
-    dec.set_profiling(False)
-    stats = [dec.stats(c) for c in chans]
+    launches, kernel_ms = 0, 0.0
+    for gr in groups:
+        nl, ms = gr["dec"].profile()
+        launches += nl
+        kernel_ms += ms
+        gr["dec"].set_profiling(False)
+    stats = all_stats()
     bad = [(c, s["status"]) for c, s in zip(chans, stats) if s["status"] != 0]
     assert not bad, f"channels stopped with an error: {bad[:5]}"
     arcs = sum(s["arcs_expanded"] for s in stats) - arcs0
@@ -136,7 +169,7 @@ def main() -> int:
     # scaled by a plain copy of known size); not measurable from inside this process
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "k_advance_config3_traffic.json")
-    if os.path.exists(tpath) and n_ch == cfg.n_streams:
+    if os.path.exists(tpath) and n_ch == cfg.n_streams and G == 1:
         with open(tpath) as f:
             tj = json.load(f)
         traffic = tj["fetch_bytes_per_launch"] + tj["write_bytes_per_launch"]
@@ -153,7 +186,7 @@ def main() -> int:
         "arcs_expanded_per_s": round(arcs / wall, 1),
         "stream_frames_per_s": round(K * n_ch * chunk / wall, 1),
         "arcs_per_stream_frame": round(arcs / (K * n_ch * chunk), 1),
-        "advance_kernel_ms_per_step": round(kernel_ms / max(launches, 1), 3),
+        "advance_kernel_ms_per_launch": round(kernel_ms / max(launches, 1), 3), "decoder_groups": G,
         "max_tokens_pre_prune": max(s["max_tokens_pre_prune"] for s in stats),
         "max_tokens": max(s["max_tokens"] for s in stats),
         "roofline": {"bound": "hbm", "kernel": "k_advance", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
@@ -163,8 +196,8 @@ def main() -> int:
                      "avg_launch_ms": round(avg_launch_s * 1e3, 4)},
         "setup_s": round(t0 - t_setup, 1),
     }
-    if last is not None:
-        result["lattice_arcs_last_chunk"] = int(last[1][-1])
+    if readout:
+        result["lattice_arcs_last_chunk"] = int(sum(l[1][-1] for l in last))
 
     if not args.no_cpu_baseline:
         import oracle

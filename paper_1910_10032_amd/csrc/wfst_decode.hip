@@ -53,6 +53,7 @@ struct wfst_decoder {
   void *d_stage2 = nullptr; size_t stage2_bytes = 0;   // scratch of the final-lattice pass
   unsigned long long *d_cnt = nullptr;
   long long *d_offs = nullptr;          // readout scratch [max(num_channels, max_lanes) + 1]
+  hipStream_t last_stream = nullptr;    // stream of the last advance call; readouts use it
   bool profiling = false;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
 };
@@ -318,6 +319,7 @@ int wfst_decode_init_channels(wfst_decoder_t *d, const int32_t *channels, int32_
   if (!d || n < 0) return WFST_E_INVALID_ARG;
   int rc = check_channels(d, channels, n, false);
   if (rc) return rc;
+  HIP_TRY(hipStreamSynchronize(d->last_stream));      // earlier work on these channels must be over
   std::vector<LaneParam> lp;
   for (int32_t i = 0; i < n; i += d->cfg.max_lanes) {
     const int32_t m = std::min(d->cfg.max_lanes, n - i);
@@ -356,13 +358,22 @@ int wfst_decode_advance(wfst_decoder_t *d, const int32_t *channels, int32_t n_la
     lp[i] = LaneParam{loglikes[i], channels[i], n_frames[i], strides[i], 0};
     d->frames_fed[channels[i]] += n_frames[i];
   }
+  d->last_stream = (hipStream_t)stream;
   return launch_lanes(d, lp, 0, (hipStream_t)stream);
+}
+
+// Readouts run on the stream of the decoder's last advance call and wait for that stream
+// only, so decoders working on different streams do not wait for each other.
+static hipError_t copy_sync(wfst_decoder *d, void *dst, const void *src, size_t bytes, hipMemcpyKind kind) {
+  hipError_t e = hipMemcpyAsync(dst, src, bytes, kind, d->last_stream);
+  if (e != hipSuccess) return e;
+  return hipStreamSynchronize(d->last_stream);
 }
 
 // Copy the channel list to the device unless it is the one already there.
 static int stage_channels(wfst_decoder *d, const int32_t *channels, int32_t n) {
   if ((int32_t)d->staged_chans.size() == n && std::memcmp(d->staged_chans.data(), channels, sizeof(int32_t) * (size_t)n) == 0) return 0;
-  HIP_TRY(hipMemcpy(d->d_chans, channels, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
+  HIP_TRY(copy_sync(d, d->d_chans, channels, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
   d->staged_chans.assign(channels, channels + n);
   return 0;
 }
@@ -375,33 +386,33 @@ int wfst_decode_best_path_batch(wfst_decoder_t *d, const int32_t *channels, int3
   if (n == 0) return 0;
   int rc = check_channels(d, channels, n, true);
   if (rc) return rc;
-  HIP_TRY(hipDeviceSynchronize());
+  HIP_TRY(hipStreamSynchronize(d->last_stream));
   rc = ensure_stage(d, sizeof(int32_t) * (size_t)n * (size_t)std::max(words_cap, 1));
   if (rc) return rc;
   rc = stage_channels(d, channels, n);
   if (rc) return rc;
-  HIP_TRY(hipMemsetAsync(d->d_cnt, 0, sizeof(unsigned long long), 0));
-  hipLaunchKernelGGL(k_best_path_words, dim3(n), dim3(64), 0, 0, d->dev, (const int32_t *)d->d_chans, use_final,
+  HIP_TRY(hipMemsetAsync(d->d_cnt, 0, sizeof(unsigned long long), d->last_stream));
+  hipLaunchKernelGGL(k_best_path_words, dim3(n), dim3(64), 0, d->last_stream, d->dev, (const int32_t *)d->d_chans, use_final,
                      (int32_t *)d->d_stage, words_cap, d->d_cnt, d->d_pathout);
   HIP_TRY(hipGetLastError());
   std::vector<PathOut> po((size_t)n);
-  HIP_TRY(hipMemcpy(po.data(), d->d_pathout, sizeof(PathOut) * (size_t)n, hipMemcpyDeviceToHost));
+  HIP_TRY(copy_sync(d, po.data(), d->d_pathout, sizeof(PathOut) * (size_t)n, hipMemcpyDeviceToHost));
   long long used = 0;
   for (int32_t i = 0; i < n; ++i) if (po[i].status == 0) used = std::max(used, po[i].word_off + po[i].n_words);
   std::vector<int32_t> w((size_t)used);
-  if (used > 0) HIP_TRY(hipMemcpy(w.data(), d->d_stage, sizeof(int32_t) * (size_t)used, hipMemcpyDeviceToHost));
+  if (used > 0) HIP_TRY(copy_sync(d, w.data(), d->d_stage, sizeof(int32_t) * (size_t)used, hipMemcpyDeviceToHost));
   for (int32_t i = 0; i < n; ++i) {
     if (po[i].status == WFST_E_CAPACITY && po[i].n_words <= words_cap) {
       // the remembered-path scratch was too small for this path: trace it in full instead
       int32_t ch = channels[i];
-      HIP_TRY(hipMemcpy(d->d_chans, &ch, sizeof(int32_t), hipMemcpyHostToDevice));
+      HIP_TRY(copy_sync(d, d->d_chans, &ch, sizeof(int32_t), hipMemcpyHostToDevice));
       d->staged_chans.clear();
-      hipLaunchKernelGGL(k_best_path, dim3(1), dim3(64), 0, 0, d->dev, (const int32_t *)d->d_chans, use_final,
+      hipLaunchKernelGGL(k_best_path, dim3(1), dim3(64), 0, d->last_stream, d->dev, (const int32_t *)d->d_chans, use_final,
                          (int32_t *)d->d_stage, words_cap, (uint32_t *)nullptr, 0, d->d_pathout);
       HIP_TRY(hipGetLastError());
-      HIP_TRY(hipMemcpy(&po[i], d->d_pathout, sizeof(PathOut), hipMemcpyDeviceToHost));
+      HIP_TRY(copy_sync(d, &po[i], d->d_pathout, sizeof(PathOut), hipMemcpyDeviceToHost));
       if (po[i].status == 0 && po[i].n_words > 0)
-        HIP_TRY(hipMemcpy(words + (size_t)i * words_cap, (int32_t *)d->d_stage + (words_cap - po[i].n_words),
+        HIP_TRY(copy_sync(d, words + (size_t)i * words_cap, (int32_t *)d->d_stage + (words_cap - po[i].n_words),
                           sizeof(int32_t) * (size_t)po[i].n_words, hipMemcpyDeviceToHost));
     } else if (po[i].status == 0 && po[i].n_words > 0) {
       std::memcpy(words + (size_t)i * words_cap, w.data() + po[i].word_off, sizeof(int32_t) * (size_t)po[i].n_words);
@@ -428,27 +439,27 @@ int wfst_decode_best_path_arcs(wfst_decoder_t *d, int32_t channel, int32_t use_f
   if (!d || cap < 0 || !n_arcs || !total_cost || !reached_final || (cap > 0 && !arcs)) return WFST_E_INVALID_ARG;
   int rc = check_channels(d, &channel, 1, true);
   if (rc) return rc;
-  HIP_TRY(hipDeviceSynchronize());
+  HIP_TRY(hipStreamSynchronize(d->last_stream));
   rc = ensure_stage(d, sizeof(uint32_t) * (size_t)std::max(cap, 1));
   if (rc) return rc;
-  HIP_TRY(hipMemcpy(d->d_chans, &channel, sizeof(int32_t), hipMemcpyHostToDevice));
+  HIP_TRY(copy_sync(d, d->d_chans, &channel, sizeof(int32_t), hipMemcpyHostToDevice));
   d->staged_chans.clear();
-  hipLaunchKernelGGL(k_best_path, dim3(1), dim3(64), 0, 0, d->dev, (const int32_t *)d->d_chans, use_final,
+  hipLaunchKernelGGL(k_best_path, dim3(1), dim3(64), 0, d->last_stream, d->dev, (const int32_t *)d->d_chans, use_final,
                      (int32_t *)nullptr, 0, cap > 0 ? (uint32_t *)d->d_stage : nullptr, cap, d->d_pathout);
   HIP_TRY(hipGetLastError());
   PathOut po;
-  HIP_TRY(hipMemcpy(&po, d->d_pathout, sizeof(PathOut), hipMemcpyDeviceToHost));
+  HIP_TRY(copy_sync(d, &po, d->d_pathout, sizeof(PathOut), hipMemcpyDeviceToHost));
   if (po.status == 0 && po.n_arcs > cap) { *n_arcs = po.n_arcs; return WFST_E_CAPACITY; }
   if (po.status) return po.status;
   if (po.n_arcs > 0)
-    HIP_TRY(hipMemcpy(arcs, (uint32_t *)d->d_stage + (cap - po.n_arcs), sizeof(uint32_t) * (size_t)po.n_arcs, hipMemcpyDeviceToHost));
+    HIP_TRY(copy_sync(d, arcs, (uint32_t *)d->d_stage + (cap - po.n_arcs), sizeof(uint32_t) * (size_t)po.n_arcs, hipMemcpyDeviceToHost));
   *n_arcs = po.n_arcs; *total_cost = po.total_cost; *reached_final = po.reached_final;
   return 0;
 }
 
 static int read_chan(wfst_decoder *d, int32_t channel, ChanState *cs) {
-  HIP_TRY(hipDeviceSynchronize());
-  HIP_TRY(hipMemcpy(cs, d->dev.chan + channel, sizeof(ChanState), hipMemcpyDeviceToHost));
+  HIP_TRY(hipStreamSynchronize(d->last_stream));
+  HIP_TRY(copy_sync(d, cs, d->dev.chan + channel, sizeof(ChanState), hipMemcpyDeviceToHost));
   return 0;
 }
 
@@ -464,21 +475,21 @@ int wfst_decode_lattice_arcs(wfst_decoder_t *d, int32_t channel, int32_t from_fr
   const long long have = cs.lat_count;
   rc = ensure_stage(d, sizeof(LatRec) * (size_t)std::max<long long>(have, 1));
   if (rc) return rc;
-  HIP_TRY(hipMemset(d->d_cnt, 0, sizeof(unsigned long long)));
+  HIP_TRY(hipMemsetAsync(d->d_cnt, 0, sizeof(unsigned long long), d->last_stream));
   if (have > 0) {
     const int blocks = (int)std::min<long long>((have + 255) / 256, 4096);
-    hipLaunchKernelGGL(k_export_lattice, dim3(blocks), dim3(256), 0, 0, d->dev, channel, have, from_frame,
+    hipLaunchKernelGGL(k_export_lattice, dim3(blocks), dim3(256), 0, d->last_stream, d->dev, channel, have, from_frame,
                        (LatRec *)d->d_stage, have, d->d_cnt);
     HIP_TRY(hipGetLastError());
   }
   unsigned long long cnt = 0;
-  HIP_TRY(hipMemcpy(&cnt, d->d_cnt, sizeof(cnt), hipMemcpyDeviceToHost));
+  HIP_TRY(copy_sync(d, &cnt, d->d_cnt, sizeof(cnt), hipMemcpyDeviceToHost));
   if ((int64_t)cnt > cap) { *n = (int64_t)cnt; return WFST_E_CAPACITY; }
   if (cnt > 0)
-    HIP_TRY(hipMemcpy(out, d->d_stage, sizeof(LatRec) * (size_t)cnt, out_is_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost));
-  hipLaunchKernelGGL(k_reset_lattice, dim3(1), dim3(1), 0, 0, d->dev, channel);
+    HIP_TRY(copy_sync(d, out, d->d_stage, sizeof(LatRec) * (size_t)cnt, out_is_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost));
+  hipLaunchKernelGGL(k_reset_lattice, dim3(1), dim3(1), 0, d->last_stream, d->dev, channel);
   HIP_TRY(hipGetLastError());
-  HIP_TRY(hipDeviceSynchronize());
+  HIP_TRY(hipStreamSynchronize(d->last_stream));
   *n = (int64_t)cnt;
   return 0;
 }
@@ -490,30 +501,28 @@ int wfst_decode_lattice_arcs_batch(wfst_decoder_t *d, const int32_t *channels, i
   if (n == 0) return 0;
   int rc = check_channels(d, channels, n, true);
   if (rc) return rc;
-  HIP_TRY(hipDeviceSynchronize());
   rc = stage_channels(d, channels, n);
   if (rc) return rc;
-  hipLaunchKernelGGL(k_lattice_offsets, dim3(1), dim3(1024), 0, 0, d->dev, (const int32_t *)d->d_chans, n, d->d_offs);
+  hipStream_t st = d->last_stream;
+  LatRec *dst = (LatRec *)out;
+  if (!out_is_device) {                 // host output goes through device staging of the caller's capacity
+    rc = ensure_stage(d, sizeof(LatRec) * (size_t)std::max<int64_t>(cap, 1));
+    if (rc) return rc;
+    dst = (LatRec *)d->d_stage;
+  }
+  // offsets, copy and reset are queued back to back; the copy and the reset check the capacity
+  // on the device, so the host waits only once
+  hipLaunchKernelGGL(k_lattice_offsets, dim3(1), dim3(1024), 0, st, d->dev, (const int32_t *)d->d_chans, n, d->d_offs);
+  hipLaunchKernelGGL(k_export_lattice_batch, dim3(n, 8), dim3(256), 0, st, d->dev, (const int32_t *)d->d_chans, n,
+                     (const long long *)d->d_offs, dst, (long long)cap);
+  hipLaunchKernelGGL(k_reset_lattice_batch, dim3((n + 255) / 256), dim3(256), 0, st, d->dev, (const int32_t *)d->d_chans, n,
+                     (const long long *)d->d_offs, (long long)cap);
   HIP_TRY(hipGetLastError());
   static_assert(sizeof(long long) == sizeof(int64_t), "offset width");
-  HIP_TRY(hipMemcpy(offsets, d->d_offs, sizeof(long long) * ((size_t)n + 1), hipMemcpyDeviceToHost));
+  HIP_TRY(copy_sync(d, offsets, d->d_offs, sizeof(long long) * ((size_t)n + 1), hipMemcpyDeviceToHost));
   const long long total = offsets[n];
   if (total > cap) return WFST_E_CAPACITY;
-  if (total > 0) {
-    LatRec *dst = (LatRec *)out;
-    if (!out_is_device) {
-      rc = ensure_stage(d, sizeof(LatRec) * (size_t)total);
-      if (rc) return rc;
-      dst = (LatRec *)d->d_stage;
-    }
-    hipLaunchKernelGGL(k_export_lattice_batch, dim3(n, 8), dim3(256), 0, 0, d->dev, (const int32_t *)d->d_chans,
-                       (const long long *)d->d_offs, dst);
-    HIP_TRY(hipGetLastError());
-    if (!out_is_device) HIP_TRY(hipMemcpy(out, dst, sizeof(LatRec) * (size_t)total, hipMemcpyDeviceToHost));
-  }
-  hipLaunchKernelGGL(k_reset_lattice_batch, dim3((n + 255) / 256), dim3(256), 0, 0, d->dev, (const int32_t *)d->d_chans, n);
-  HIP_TRY(hipGetLastError());
-  HIP_TRY(hipDeviceSynchronize());
+  if (!out_is_device && total > 0) HIP_TRY(copy_sync(d, out, dst, sizeof(LatRec) * (size_t)total, hipMemcpyDeviceToHost));
   return 0;
 }
 
@@ -544,15 +553,15 @@ int wfst_decode_final_lattice(wfst_decoder_t *d, int32_t channel, int32_t use_fi
     dst = (LatRec *)d->d_stage;
   }
   char *base = (char *)d->d_stage2;
-  hipLaunchKernelGGL(k_final_lattice, dim3(1), dim3(1024), 0, 0, d->dev, channel, use_final, (uint32_t *)base,
+  hipLaunchKernelGGL(k_final_lattice, dim3(1), dim3(1024), 0, d->last_stream, d->dev, channel, use_final, (uint32_t *)base,
                      (long long *)(base + rs_off), dst, (long long)cap, (LatticeInfoDev *)(base + info_off));
   HIP_TRY(hipGetLastError());
   LatticeInfoDev li;
-  HIP_TRY(hipMemcpy(&li, base + info_off, sizeof(li), hipMemcpyDeviceToHost));
+  HIP_TRY(copy_sync(d, &li, base + info_off, sizeof(li), hipMemcpyDeviceToHost));
   if (li.status == WFST_E_CAPACITY) { *n = li.arcs_kept; return WFST_E_CAPACITY; }
   if (li.status != 0) return li.status;
   if (!out_is_device && li.arcs_kept > 0)
-    HIP_TRY(hipMemcpy(out, dst, sizeof(LatRec) * (size_t)li.arcs_kept, hipMemcpyDeviceToHost));
+    HIP_TRY(copy_sync(d, out, dst, sizeof(LatRec) * (size_t)li.arcs_kept, hipMemcpyDeviceToHost));
   *n = li.arcs_kept;
   info->arcs_in = li.arcs_in; info->arcs_kept = li.arcs_kept; info->frames = li.frames;
   info->reached_final = li.reached_final; info->best_cost = li.best_cost;
@@ -570,15 +579,15 @@ int wfst_decode_tokens(wfst_decoder_t *d, int32_t channel, int32_t frame, wfst_t
   if (frame < 0) frame += cs.num_frames;
   if (frame < 0 || frame >= cs.num_frames) return WFST_E_INVALID_ARG;
   long long off[2];
-  HIP_TRY(hipMemcpy(off, d->dev.frame_off + (size_t)channel * (size_t)(d->cfg.max_frames + 2) + frame, sizeof(off), hipMemcpyDeviceToHost));
+  HIP_TRY(copy_sync(d, off, d->dev.frame_off + (size_t)channel * (size_t)(d->cfg.max_frames + 2) + frame, sizeof(off), hipMemcpyDeviceToHost));
   const int cnt = (int)(off[1] - off[0]);
   if (cnt > cap) { *n = cnt; return WFST_E_CAPACITY; }
   if (cnt > 0) {
     rc = ensure_stage(d, sizeof(TokOut) * (size_t)cnt);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_export_tokens, dim3((cnt + 255) / 256), dim3(256), 0, 0, d->dev, channel, off[0], cnt, (TokOut *)d->d_stage);
+    hipLaunchKernelGGL(k_export_tokens, dim3((cnt + 255) / 256), dim3(256), 0, d->last_stream, d->dev, channel, off[0], cnt, (TokOut *)d->d_stage);
     HIP_TRY(hipGetLastError());
-    HIP_TRY(hipMemcpy(out, d->d_stage, sizeof(TokOut) * (size_t)cnt, hipMemcpyDeviceToHost));
+    HIP_TRY(copy_sync(d, out, d->d_stage, sizeof(TokOut) * (size_t)cnt, hipMemcpyDeviceToHost));
   }
   *n = cnt;
   return 0;

@@ -809,9 +809,11 @@ __global__ void __launch_bounds__(64) k_best_path_words(DecDev D, const int32_t 
     const int cached_nf = cs->path_nf;
     int f = F, k = 0, base = 0, merge_f = 0, status = 0;
     const long long max_steps = cs->hist_used + 1;
-    for (long long step = 0;; ++step) {
-      if (cur < 0 || (long long)cur >= foff[f + 1] - foff[f]) { status = E_BROKEN_TRACE; break; }
-      const HTok t = hist[foff[f] + cur];
+    // the token of the next step is fetched while this step's word label is still on its way
+    auto in_frame = [&](int ff, int c) { return ff >= 0 && c >= 0 && (long long)c < foff[ff + 1] - foff[ff]; };
+    HTok t{};
+    if (!in_frame(f, cur)) status = E_BROKEN_TRACE; else t = hist[foff[f] + cur];
+    for (long long step = 0; status == 0; ++step) {
       if (t.in_arc == NO_ARC) break;
       if (t.prev == NO_ARC || step > max_steps) { status = E_BROKEN_TRACE; break; }
       const bool is_entry = !(t.prev & PREV_SAME);
@@ -820,12 +822,17 @@ __global__ void __launch_bounds__(64) k_best_path_words(DecDev D, const int32_t 
         entry[f] = cur; wcount[f] = k;        // k: words found so far, all later on the path; fixed up below
       }
       const int32_t w = D.g.label[t.in_arc];
+      const int ncur = is_entry ? (int)t.prev : (int)(t.prev & ~PREV_SAME);
+      const int nf = is_entry ? f - 1 : f;
+      HTok tn{};
+      const bool ok = in_frame(nf, ncur);
+      if (ok) tn = hist[foff[nf] + ncur];
       if (w != 0) {
         if (k < D.pc_wcap) cw[D.pc_wcap - 1 - k] = w;
         ++k;
       }
-      if (is_entry) { cur = (int)t.prev; --f; if (f < 0) { status = E_BROKEN_TRACE; break; } }
-      else cur = (int)(t.prev & ~PREV_SAME);
+      if (!ok) { status = E_BROKEN_TRACE; break; }
+      cur = ncur; f = nf; t = tn;
     }
     if (status == 0 && (long long)base + 2ll * k > (long long)D.pc_wcap) status = E_CAPACITY;
     sh[0] = status; sh[1] = base + k; sh[2] = merge_f; sh[3] = k;
@@ -911,7 +918,8 @@ __global__ void __launch_bounds__(1024) k_lattice_offsets(DecDev D, const int32_
   }
   if (tid == 1023) offs[n] = part[1023];
 }
-__global__ void k_export_lattice_batch(DecDev D, const int32_t *chans, const long long *offs, LatRec *out) {
+__global__ void k_export_lattice_batch(DecDev D, const int32_t *chans, int n_ch, const long long *offs, LatRec *out, long long cap) {
+  if (offs[n_ch] > cap) return;                       // caller's buffer too small: nothing is copied or drained
   const int ch = chans[blockIdx.x];
   const LatInt *lat = D.lat + (size_t)ch * (size_t)D.lat_cap;
   const long long o = offs[blockIdx.x], n = offs[blockIdx.x + 1] - o;
@@ -920,7 +928,8 @@ __global__ void k_export_lattice_batch(DecDev D, const int32_t *chans, const lon
     out[o + i] = LatRec{r.frame, D.g.orig[r.arc], r.extra};
   }
 }
-__global__ void k_reset_lattice_batch(DecDev D, const int32_t *chans, int n) {
+__global__ void k_reset_lattice_batch(DecDev D, const int32_t *chans, int n, const long long *offs, long long cap) {
+  if (offs[n] > cap) return;
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) D.chan[chans[i]].lat_count = 0;
 }
