@@ -6,9 +6,11 @@ Workload: benchmark configs[3] — the 8M-state / 23M-arc synthetic decoding
 with a best-path and a lattice-arc readout for every channel after every chunk.
 
 A "step" is one pass of the whole hot path over one batch: all 500 lanes advance by one
-50-frame chunk (emitting expansion, closure, pruning, lattice records), followed by the
-per-chunk readouts.  Scores are generated on the device beforehand and are resident in
-HBM when the timed region starts.  value = seconds of audio decoded per wall second at
+50-frame chunk (emitting expansion, closure, pruning, lattice records), and the per-chunk
+readouts of that chunk (best path and lattice arcs of every channel).  The readouts work on
+a snapshot sealed behind the chunk and run beside the next chunk's decoding (the paper's
+second stream, Section 3); --sync-readout makes them wait for each other instead.  Scores
+are generated on the device beforehand and are resident in HBM when the timed region starts.  value = seconds of audio decoded per wall second at
 10 ms per frame (RTFx), whole job.
 
 Prints ONE JSON line.
@@ -41,7 +43,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-readout", action="store_true", help="time the advance calls only")
     ap.add_argument("--cpu-streams", type=int, default=12)
-    ap.add_argument("--groups", type=int, default=1, help="decoder groups the channels are split into (staggered)")
+    ap.add_argument("--sync-readout", action="store_true",
+                    help="read each chunk out before the next one is queued (no overlap with decoding)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 1 GiB device copy (calibrates the HBM byte counters under rocprofv3)")
     args = ap.parse_args()
@@ -76,82 +79,67 @@ def main() -> int:
     P = cfg.graph.num_pdfs
 
     t_setup = time.perf_counter()
-    G = max(1, min(args.groups, n_ch))
     g = synth.make_graph(cfg.graph)
     graph = B.WfstGraph(g)
-    # The channels are split into G groups, each with its own decoder and stream.  The groups
-    # run staggered: while the host reads out one group's chunk, the others are decoding, so
-    # the per-chunk readouts do not stall the GPU (the paper's second-stream idea, Section 3).
-    bounds = [n_ch * k // G for k in range(G + 1)]
     scores = torch.empty((n_ch, n_frames, P), dtype=torch.float32, device="cuda")
     for s in range(n_ch):
         synth.device_loglikes(scores[s], cfg.ll_seed, s, 0, cfg.ll_mu, cfg.ll_sigma, cfg.ll_boost)
     torch.cuda.synchronize()
-    groups = []
-    for k in range(G):
-        lo, hi = bounds[k], bounds[k + 1]
-        n = hi - lo
-        dec = B.WfstDecoder(graph, cfg.beam, cfg.lattice_beam, cfg.max_active, num_channels=n, max_lanes=n,
-                            max_frames=n_frames, token_capacity=16384, history_capacity=2_500_000,
-                            lattice_capacity=400_000)
-        ch_np = np.arange(n, dtype=np.int32)
-        dec.init_channels(ch_np)
-        groups.append(dict(dec=dec, ch=ch_np, n=n, stream=torch.cuda.Stream().cuda_stream,
-                           strides=np.full(n, P, np.int32), nfr=np.full(n, chunk, np.int32),
-                           row0=scores.data_ptr() + np.arange(lo, hi, dtype=np.uint64) * np.uint64(n_frames * P * 4),
-                           lat_buf=torch.empty(n * 80_000 * 12, dtype=torch.uint8, device="cuda")))
+    dec = B.WfstDecoder(graph, cfg.beam, cfg.lattice_beam, cfg.max_active, num_channels=n_ch, max_lanes=n_ch,
+                        max_frames=n_frames, token_capacity=16384, history_capacity=2_500_000,
+                        lattice_capacity=400_000)
+    ch_np = np.arange(n_ch, dtype=np.int32)
+    dec.init_channels(ch_np)
+    stream = torch.cuda.Stream().cuda_stream
+    strides, nfr = np.full(n_ch, P, np.int32), np.full(n_ch, chunk, np.int32)
+    row0 = scores.data_ptr() + np.arange(n_ch, dtype=np.uint64) * np.uint64(n_frames * P * 4)
+    lat_buf = torch.empty(n_ch * 80_000 * 12, dtype=torch.uint8, device="cuda")
     chans = list(range(n_ch))
     readout = not args.no_readout
+    overlap = readout and not args.sync_readout
 
-    def launch(gr, i: int):
-        gr["dec"].advance_ptrs(gr["ch"], gr["row0"] + np.uint64(i * chunk * P * 4), gr["strides"], gr["nfr"], gr["stream"])
+    def launch(i: int):
+        dec.advance_ptrs(ch_np, row0 + np.uint64(i * chunk * P * 4), strides, nfr, stream)
 
-    def read(gr):
-        if not readout:
-            return None
-        paths = gr["dec"].best_path_batch(gr["ch"], use_final=False, words_cap=1024, raw=True)
-        offs = gr["dec"].lattice_arcs_batch(gr["ch"], out_device=gr["lat_buf"])
+    def read():
+        paths = dec.best_path_batch(ch_np, use_final=False, words_cap=1024, raw=True, snapshot=overlap)
+        offs = dec.lattice_arcs_batch(ch_np, out_device=lat_buf, snapshot=overlap)
         return paths, offs
 
     def all_stats():
-        return [gr["dec"].stats(int(c)) for gr in groups for c in gr["ch"]]
+        return [dec.stats(int(c)) for c in ch_np]
 
-    def run(first: int, count: int, offset_s: float = 0.0):
-        """Steps [first, first + count): every group advances one chunk per step and is read out.
-        offset_s spaces the groups' first launches so that their chunks complete at different
-        times (the delay is inside the timed region)."""
-        last = [None] * G
-        for k, gr in enumerate(groups):
-            if k and offset_s > 0:
-                time.sleep(offset_s)
-            launch(gr, first)
+    def run(first: int, count: int):
+        """Steps [first, first + count): chunk i is decoded, sealed and read out; with overlap
+        chunk i + 1 is queued before chunk i is read, so it decodes during the readout."""
+        last = None
+        launch(first)
         for i in range(first, first + count):
-            for k, gr in enumerate(groups):
-                last[k] = read(gr)                 # waits for this group's chunk i only
-                if i + 1 < first + count:
-                    launch(gr, i + 1)              # its next chunk decodes while the other groups are read
+            more = i + 1 < first + count
+            if overlap:
+                dec.snapshot()
+                if more:
+                    launch(i + 1)
+                last = read()
+            else:
+                if readout:
+                    last = read()
+                if more:
+                    launch(i + 1)
         torch.cuda.synchronize()
         return last
 
-    offset_s = 0.0
     if W:
-        tw = time.perf_counter()
         run(0, W)
-        offset_s = (time.perf_counter() - tw) / W / G if G > 1 else 0.0
     stats0 = all_stats()
     arcs0 = sum(s["arcs_expanded"] for s in stats0)
-    for gr in groups:
-        gr["dec"].set_profiling(True)
+    dec.set_profiling(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    last = run(W, K, offset_s)
+    last = run(W, K)
     t1 = time.perf_counter()
-    launches, kernel_ms = 0, 0.0
-    for gr in groups:
-        nl, ms = gr["dec"].profile()
-        launches += nl
-        kernel_ms += ms
-        gr["dec"].set_profiling(False)
+    launches, kernel_ms = dec.profile()
+    dec.set_profiling(False)
     stats = all_stats()
     bad = [(c, s["status"]) for c, s in zip(chans, stats) if s["status"] != 0]
     assert not bad, f"channels stopped with an error: {bad[:5]}"
@@ -169,7 +157,7 @@ def main() -> int:
     # scaled by a plain copy of known size); not measurable from inside this process
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "k_advance_config3_traffic.json")
-    if os.path.exists(tpath) and n_ch == cfg.n_streams and G == 1:
+    if os.path.exists(tpath) and n_ch == cfg.n_streams:
         with open(tpath) as f:
             tj = json.load(f)
         traffic = tj["fetch_bytes_per_launch"] + tj["write_bytes_per_launch"]
@@ -181,12 +169,12 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "configs[3]: 8M-state/23M-arc synthetic graph, %d channels x %d-frame chunks, beam %g, "
                                "max-active %d, lattice-beam %g, per-chunk best-path + lattice readout%s"
-                               % (n_ch, chunk, cfg.beam, cfg.max_active, cfg.lattice_beam, "" if readout else " (readout off)"),
+                               % (n_ch, chunk, cfg.beam, cfg.max_active, cfg.lattice_beam, ("" if overlap else " (not overlapped)") if readout else " (readout off)"),
                    "channels": n_ch, "chunk_frames": chunk, "stream_frames_timed": K * n_ch * chunk},
         "arcs_expanded_per_s": round(arcs / wall, 1),
         "stream_frames_per_s": round(K * n_ch * chunk / wall, 1),
         "arcs_per_stream_frame": round(arcs / (K * n_ch * chunk), 1),
-        "advance_kernel_ms_per_launch": round(kernel_ms / max(launches, 1), 3), "decoder_groups": G,
+        "advance_kernel_ms_per_launch": round(kernel_ms / max(launches, 1), 3), "readout_overlapped": bool(overlap),
         "max_tokens_pre_prune": max(s["max_tokens_pre_prune"] for s in stats),
         "max_tokens": max(s["max_tokens"] for s in stats),
         "roofline": {"bound": "hbm", "kernel": "k_advance", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
@@ -197,7 +185,7 @@ def main() -> int:
         "setup_s": round(t0 - t_setup, 1),
     }
     if readout:
-        result["lattice_arcs_last_chunk"] = int(sum(l[1][-1] for l in last))
+        result["lattice_arcs_last_chunk"] = int(last[1][-1])
 
     if not args.no_cpu_baseline:
         import oracle

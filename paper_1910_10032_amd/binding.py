@@ -24,7 +24,8 @@ EXPORTS = [
     "wfst_decode_graph_load", "wfst_decode_graph_free", "wfst_decode_graph_bytes", "wfst_decode_create",
     "wfst_decode_destroy", "wfst_decode_state_bytes", "wfst_decode_init_channels", "wfst_decode_free_channels",
     "wfst_decode_advance", "wfst_decode_best_path_batch", "wfst_decode_best_path", "wfst_decode_best_path_arcs",
-    "wfst_decode_lattice_arcs", "wfst_decode_lattice_arcs_batch", "wfst_decode_final_lattice", "wfst_decode_tokens", "wfst_decode_stats", "wfst_decode_set_profiling",
+    "wfst_decode_lattice_arcs", "wfst_decode_lattice_arcs_batch", "wfst_decode_snapshot",
+    "wfst_decode_snapshot_best_path_batch", "wfst_decode_snapshot_lattice_arcs_batch", "wfst_decode_final_lattice", "wfst_decode_tokens", "wfst_decode_stats", "wfst_decode_set_profiling",
     "wfst_decode_profile", "wfst_decode_strerror",
 ]
 
@@ -85,6 +86,9 @@ def lib():
         L.wfst_decode_best_path_arcs.argtypes = [vp, i32, i32, vp, i32, C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(i32)]
         L.wfst_decode_lattice_arcs.argtypes = [vp, i32, i32, vp, i64, C.POINTER(i64), i32]
         L.wfst_decode_lattice_arcs_batch.argtypes = [vp, vp, i32, vp, i64, vp, i32]
+        L.wfst_decode_snapshot.argtypes = [vp]
+        L.wfst_decode_snapshot_best_path_batch.argtypes = L.wfst_decode_best_path_batch.argtypes
+        L.wfst_decode_snapshot_lattice_arcs_batch.argtypes = L.wfst_decode_lattice_arcs_batch.argtypes
         L.wfst_decode_final_lattice.argtypes = [vp, i32, i32, vp, i64, C.POINTER(i64), i32, C.POINTER(wfst_lattice_info_t)]
         L.wfst_decode_tokens.argtypes = [vp, i32, i32, vp, i32, C.POINTER(i32)]
         L.wfst_decode_stats.argtypes = [vp, i32, C.POINTER(wfst_stats_t)]
@@ -202,26 +206,30 @@ class WfstDecoder:
                                          strides.ctypes.data, n_frames.ctypes.data, C.c_void_p(stream)),
                "wfst_decode_advance")
 
-    def best_path_batch(self, channels, use_final: bool = True, words_cap: int = 4096, raw: bool = False):
+    def snapshot(self):
+        _check(lib().wfst_decode_snapshot(self.h), "wfst_decode_snapshot")
+
+    def best_path_batch(self, channels, use_final: bool = True, words_cap: int = 4096, raw: bool = False,
+                        snapshot: bool = False):
         """Per channel: dict(status, words, total_cost, reached_final); with raw=True the
-        arrays (words [n, cap], n_words, total_cost, reached_final, status) as filled by the call."""
+        arrays (words [n, cap], n_words, total_cost, reached_final, status) as filled by the call.
+        snapshot=True reads the state sealed by the last snapshot() call."""
         ch = np.ascontiguousarray(channels, np.int32)
         n = len(ch)
+        fn = lib().wfst_decode_snapshot_best_path_batch if snapshot else lib().wfst_decode_best_path_batch
         if raw:
             words = np.empty((n, max(words_cap, 1)), np.int32)
             nw, tc = np.empty(n, np.int32), np.empty(n, np.float32)
             rf, st = np.empty(n, np.int32), np.empty(n, np.int32)
-            _check(lib().wfst_decode_best_path_batch(self.h, ch.ctypes.data, n, int(use_final), words.ctypes.data,
-                                                     words_cap, nw.ctypes.data, tc.ctypes.data, rf.ctypes.data,
-                                                     st.ctypes.data), "wfst_decode_best_path_batch")
+            _check(fn(self.h, ch.ctypes.data, n, int(use_final), words.ctypes.data, words_cap, nw.ctypes.data,
+                      tc.ctypes.data, rf.ctypes.data, st.ctypes.data), "wfst_decode_best_path_batch")
             return words, nw, tc, rf, st
         while True:
             words = np.zeros((n, max(words_cap, 1)), np.int32)
             nw, tc = np.zeros(n, np.int32), np.zeros(n, np.float32)
             rf, st = np.zeros(n, np.int32), np.zeros(n, np.int32)
-            _check(lib().wfst_decode_best_path_batch(self.h, ch.ctypes.data, n, int(use_final), words.ctypes.data,
-                                                     words_cap, nw.ctypes.data, tc.ctypes.data, rf.ctypes.data,
-                                                     st.ctypes.data), "wfst_decode_best_path_batch")
+            _check(fn(self.h, ch.ctypes.data, n, int(use_final), words.ctypes.data, words_cap, nw.ctypes.data,
+                      tc.ctypes.data, rf.ctypes.data, st.ctypes.data), "wfst_decode_best_path_batch")
             if (st == WFST_E_CAPACITY).any():
                 words_cap = int(nw.max())
                 continue
@@ -270,20 +278,21 @@ class WfstDecoder:
             _check(rc, "wfst_decode_lattice_arcs")
             return out[:n.value].copy()
 
-    def lattice_arcs_batch(self, channels, cap: int = 1 << 20, out_device=None):
+    def lattice_arcs_batch(self, channels, cap: int = 1 << 20, out_device=None, snapshot: bool = False):
         """Drains several channels: (records, offsets) on the host, or offsets only when the
-        records go into the cuda tensor `out_device`."""
+        records go into the cuda tensor `out_device`.  snapshot=True drains the arcs sealed by
+        the last snapshot() call."""
+        fn = lib().wfst_decode_snapshot_lattice_arcs_batch if snapshot else lib().wfst_decode_lattice_arcs_batch
         ch = np.ascontiguousarray(channels, np.int32)
         offs = np.zeros(len(ch) + 1, np.int64)
         while True:
             if out_device is not None:
                 cap = out_device.numel() * out_device.element_size() // LAT_DTYPE.itemsize
-                _check(lib().wfst_decode_lattice_arcs_batch(self.h, ch.ctypes.data, len(ch), out_device.data_ptr(), cap,
-                                                            offs.ctypes.data, 1), "wfst_decode_lattice_arcs_batch")
+                _check(fn(self.h, ch.ctypes.data, len(ch), out_device.data_ptr(), cap, offs.ctypes.data, 1),
+                       "wfst_decode_lattice_arcs_batch")
                 return offs
             out = np.zeros(max(cap, 1), LAT_DTYPE)
-            rc = lib().wfst_decode_lattice_arcs_batch(self.h, ch.ctypes.data, len(ch), out.ctypes.data, cap,
-                                                      offs.ctypes.data, 0)
+            rc = fn(self.h, ch.ctypes.data, len(ch), out.ctypes.data, cap, offs.ctypes.data, 0)
             if rc == WFST_E_CAPACITY:
                 cap = int(offs[-1])
                 continue

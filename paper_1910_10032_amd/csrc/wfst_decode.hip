@@ -54,6 +54,10 @@ struct wfst_decoder {
   unsigned long long *d_cnt = nullptr;
   long long *d_offs = nullptr;          // readout scratch [max(num_channels, max_lanes) + 1]
   hipStream_t last_stream = nullptr;    // stream of the last advance call; readouts use it
+  hipStream_t side_stream = nullptr;    // snapshot readouts run here, beside the decoding
+  hipEvent_t ev_snap = nullptr;         // the last snapshot has been taken
+  hipEvent_t ev_read = nullptr;         // the last snapshot readout has finished
+  bool have_snapshot = false;
   bool profiling = false;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
 };
@@ -281,6 +285,9 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
     for (int i = 0; ok && i < PARAM_RING; ++i)
       ok = hipHostMalloc((void **)&d->h_params[i], sizeof(LaneParam) * nl) == hipSuccess &&
            hipEventCreateWithFlags(&d->param_ev[i], hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipStreamCreateWithFlags(&d->side_stream, hipStreamNonBlocking) == hipSuccess &&
+         hipEventCreateWithFlags(&d->ev_snap, hipEventDisableTiming) == hipSuccess &&
+         hipEventCreateWithFlags(&d->ev_read, hipEventDisableTiming) == hipSuccess;
     if (ok) {
       hipLaunchKernelGGL(k_fill_slots, dim3(1024), dim3(256), 0, 0, D.slots, nl * (size_t)D.H);
       ok = hipGetLastError() == hipSuccess && hipDeviceSynchronize() == hipSuccess;
@@ -304,6 +311,9 @@ void wfst_decode_destroy(wfst_decoder_t *d) {
     if (d->param_ev[i]) (void)hipEventDestroy(d->param_ev[i]);
   }
   for (auto &p : d->prof_events) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
+  if (d->ev_snap) (void)hipEventDestroy(d->ev_snap);
+  if (d->ev_read) (void)hipEventDestroy(d->ev_read);
+  if (d->side_stream) (void)hipStreamDestroy(d->side_stream);
   delete d;
 }
 
@@ -320,6 +330,7 @@ int wfst_decode_init_channels(wfst_decoder_t *d, const int32_t *channels, int32_
   int rc = check_channels(d, channels, n, false);
   if (rc) return rc;
   HIP_TRY(hipStreamSynchronize(d->last_stream));      // earlier work on these channels must be over
+  HIP_TRY(hipStreamSynchronize(d->side_stream));
   std::vector<LaneParam> lp;
   for (int32_t i = 0; i < n; i += d->cfg.max_lanes) {
     const int32_t m = std::min(d->cfg.max_lanes, n - i);
@@ -364,21 +375,34 @@ int wfst_decode_advance(wfst_decoder_t *d, const int32_t *channels, int32_t n_la
 
 // Readouts run on the stream of the decoder's last advance call and wait for that stream
 // only, so decoders working on different streams do not wait for each other.
-static hipError_t copy_sync(wfst_decoder *d, void *dst, const void *src, size_t bytes, hipMemcpyKind kind) {
-  hipError_t e = hipMemcpyAsync(dst, src, bytes, kind, d->last_stream);
+static hipError_t copy_sync_on(hipStream_t st, void *dst, const void *src, size_t bytes, hipMemcpyKind kind) {
+  hipError_t e = hipMemcpyAsync(dst, src, bytes, kind, st);
   if (e != hipSuccess) return e;
-  return hipStreamSynchronize(d->last_stream);
+  return hipStreamSynchronize(st);
+}
+static hipError_t copy_sync(wfst_decoder *d, void *dst, const void *src, size_t bytes, hipMemcpyKind kind) {
+  return copy_sync_on(d->last_stream, dst, src, bytes, kind);
+}
+
+// Stream a readout runs on.  A snapshot readout runs on the decoder's side stream once the
+// snapshot has been taken; it does not wait for decoding queued after the snapshot.
+static int readout_stream(wfst_decoder *d, bool snap, hipStream_t *st) {
+  if (!snap) { *st = d->last_stream; return 0; }
+  if (!d->have_snapshot) return WFST_E_NOT_INIT;
+  HIP_TRY(hipStreamWaitEvent(d->side_stream, d->ev_snap, 0));
+  *st = d->side_stream;
+  return 0;
 }
 
 // Copy the channel list to the device unless it is the one already there.
-static int stage_channels(wfst_decoder *d, const int32_t *channels, int32_t n) {
+static int stage_channels(wfst_decoder *d, hipStream_t st, const int32_t *channels, int32_t n) {
   if ((int32_t)d->staged_chans.size() == n && std::memcmp(d->staged_chans.data(), channels, sizeof(int32_t) * (size_t)n) == 0) return 0;
-  HIP_TRY(copy_sync(d, d->d_chans, channels, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
+  HIP_TRY(copy_sync_on(st, d->d_chans, channels, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
   d->staged_chans.assign(channels, channels + n);
   return 0;
 }
 
-int wfst_decode_best_path_batch(wfst_decoder_t *d, const int32_t *channels, int32_t n, int32_t use_final,
+static int best_path_batch_impl(wfst_decoder_t *d, bool snap, const int32_t *channels, int32_t n, int32_t use_final,
                                 int32_t *words, int32_t words_cap, int32_t *n_words, float *total_cost,
                                 int32_t *reached_final, int32_t *status) {
   if (!d || n < 0 || words_cap < 0 || (n > 0 && (!n_words || !total_cost || !reached_final || !status))) return WFST_E_INVALID_ARG;
@@ -386,41 +410,74 @@ int wfst_decode_best_path_batch(wfst_decoder_t *d, const int32_t *channels, int3
   if (n == 0) return 0;
   int rc = check_channels(d, channels, n, true);
   if (rc) return rc;
-  HIP_TRY(hipStreamSynchronize(d->last_stream));
-  rc = ensure_stage(d, sizeof(int32_t) * (size_t)n * (size_t)std::max(words_cap, 1));
+  hipStream_t st = nullptr;
+  rc = readout_stream(d, snap, &st);
   if (rc) return rc;
-  rc = stage_channels(d, channels, n);
+  const int sn = snap ? 1 : 0;
+  if (sizeof(int32_t) * (size_t)n * (size_t)std::max(words_cap, 1) > d->stage_bytes) {
+    HIP_TRY(hipStreamSynchronize(st));            // the staging buffer is about to be replaced
+    rc = ensure_stage(d, sizeof(int32_t) * (size_t)n * (size_t)std::max(words_cap, 1));
+    if (rc) return rc;
+  }
+  rc = stage_channels(d, st, channels, n);
   if (rc) return rc;
-  HIP_TRY(hipMemsetAsync(d->d_cnt, 0, sizeof(unsigned long long), d->last_stream));
-  hipLaunchKernelGGL(k_best_path_words, dim3(n), dim3(64), 0, d->last_stream, d->dev, (const int32_t *)d->d_chans, use_final,
+  HIP_TRY(hipMemsetAsync(d->d_cnt, 0, sizeof(unsigned long long), st));
+  hipLaunchKernelGGL(k_best_path_words, dim3(n), dim3(64), 0, st, d->dev, (const int32_t *)d->d_chans, use_final, sn,
                      (int32_t *)d->d_stage, words_cap, d->d_cnt, d->d_pathout);
   HIP_TRY(hipGetLastError());
   std::vector<PathOut> po((size_t)n);
-  HIP_TRY(copy_sync(d, po.data(), d->d_pathout, sizeof(PathOut) * (size_t)n, hipMemcpyDeviceToHost));
+  HIP_TRY(copy_sync_on(st, po.data(), d->d_pathout, sizeof(PathOut) * (size_t)n, hipMemcpyDeviceToHost));
   long long used = 0;
   for (int32_t i = 0; i < n; ++i) if (po[i].status == 0) used = std::max(used, po[i].word_off + po[i].n_words);
   std::vector<int32_t> w((size_t)used);
-  if (used > 0) HIP_TRY(copy_sync(d, w.data(), d->d_stage, sizeof(int32_t) * (size_t)used, hipMemcpyDeviceToHost));
+  if (used > 0) HIP_TRY(copy_sync_on(st, w.data(), d->d_stage, sizeof(int32_t) * (size_t)used, hipMemcpyDeviceToHost));
   for (int32_t i = 0; i < n; ++i) {
     if (po[i].status == WFST_E_CAPACITY && po[i].n_words <= words_cap) {
       // the remembered-path scratch was too small for this path: trace it in full instead
       int32_t ch = channels[i];
-      HIP_TRY(copy_sync(d, d->d_chans, &ch, sizeof(int32_t), hipMemcpyHostToDevice));
+      HIP_TRY(copy_sync_on(st, d->d_chans, &ch, sizeof(int32_t), hipMemcpyHostToDevice));
       d->staged_chans.clear();
-      hipLaunchKernelGGL(k_best_path, dim3(1), dim3(64), 0, d->last_stream, d->dev, (const int32_t *)d->d_chans, use_final,
+      hipLaunchKernelGGL(k_best_path, dim3(1), dim3(64), 0, st, d->dev, (const int32_t *)d->d_chans, use_final, sn,
                          (int32_t *)d->d_stage, words_cap, (uint32_t *)nullptr, 0, d->d_pathout);
       HIP_TRY(hipGetLastError());
-      HIP_TRY(copy_sync(d, &po[i], d->d_pathout, sizeof(PathOut), hipMemcpyDeviceToHost));
+      HIP_TRY(copy_sync_on(st, &po[i], d->d_pathout, sizeof(PathOut), hipMemcpyDeviceToHost));
       if (po[i].status == 0 && po[i].n_words > 0)
-        HIP_TRY(copy_sync(d, words + (size_t)i * words_cap, (int32_t *)d->d_stage + (words_cap - po[i].n_words),
+        HIP_TRY(copy_sync_on(st, words + (size_t)i * words_cap, (int32_t *)d->d_stage + (words_cap - po[i].n_words),
                           sizeof(int32_t) * (size_t)po[i].n_words, hipMemcpyDeviceToHost));
     } else if (po[i].status == 0 && po[i].n_words > 0) {
       std::memcpy(words + (size_t)i * words_cap, w.data() + po[i].word_off, sizeof(int32_t) * (size_t)po[i].n_words);
     }
     status[i] = po[i].status; n_words[i] = po[i].n_words; total_cost[i] = po[i].total_cost; reached_final[i] = po[i].reached_final;
   }
+  if (snap) HIP_TRY(hipEventRecord(d->ev_read, st));
   return 0;
 }
+
+int wfst_decode_best_path_batch(wfst_decoder_t *d, const int32_t *channels, int32_t n, int32_t use_final,
+                                int32_t *words, int32_t words_cap, int32_t *n_words, float *total_cost,
+                                int32_t *reached_final, int32_t *status) {
+  return best_path_batch_impl(d, false, channels, n, use_final, words, words_cap, n_words, total_cost, reached_final, status);
+}
+
+int wfst_decode_snapshot_best_path_batch(wfst_decoder_t *d, const int32_t *channels, int32_t n, int32_t use_final,
+                                         int32_t *words, int32_t words_cap, int32_t *n_words, float *total_cost,
+                                         int32_t *reached_final, int32_t *status) {
+  return best_path_batch_impl(d, true, channels, n, use_final, words, words_cap, n_words, total_cost, reached_final, status);
+}
+
+int wfst_decode_snapshot(wfst_decoder_t *d) {
+  if (!d) return WFST_E_INVALID_ARG;
+  // the previous snapshot's readouts must be over before its fields are replaced
+  HIP_TRY(hipStreamWaitEvent(d->last_stream, d->ev_read, 0));
+  const int nc = d->cfg.num_channels;
+  hipLaunchKernelGGL(k_snapshot, dim3((nc + 255) / 256), dim3(256), 0, d->last_stream, d->dev, nc);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipEventRecord(d->ev_snap, d->last_stream));
+  d->have_snapshot = true;
+  return 0;
+}
+
+
 
 int wfst_decode_best_path(wfst_decoder_t *d, int32_t channel, int32_t use_final, int32_t *words, int32_t cap,
                           int32_t *n_words, float *total_cost, int32_t *reached_final) {
@@ -444,7 +501,7 @@ int wfst_decode_best_path_arcs(wfst_decoder_t *d, int32_t channel, int32_t use_f
   if (rc) return rc;
   HIP_TRY(copy_sync(d, d->d_chans, &channel, sizeof(int32_t), hipMemcpyHostToDevice));
   d->staged_chans.clear();
-  hipLaunchKernelGGL(k_best_path, dim3(1), dim3(64), 0, d->last_stream, d->dev, (const int32_t *)d->d_chans, use_final,
+  hipLaunchKernelGGL(k_best_path, dim3(1), dim3(64), 0, d->last_stream, d->dev, (const int32_t *)d->d_chans, use_final, 0,
                      (int32_t *)nullptr, 0, cap > 0 ? (uint32_t *)d->d_stage : nullptr, cap, d->d_pathout);
   HIP_TRY(hipGetLastError());
   PathOut po;
@@ -472,14 +529,17 @@ int wfst_decode_lattice_arcs(wfst_decoder_t *d, int32_t channel, int32_t from_fr
   rc = read_chan(d, channel, &cs);
   if (rc) return rc;
   if (cs.status != 0 && cs.status != WFST_E_DEAD_CHANNEL && cs.status != WFST_E_NAN_INPUT) return cs.status;
-  const long long have = cs.lat_count;
+  // an undrained snapshot first, then the current epoch
+  const long long seg_lo[2] = {cs.snap_lo, cs.lat_start}, seg_n[2] = {cs.snap_hi - cs.snap_lo, cs.lat_count};
+  const long long have = seg_n[0] + seg_n[1];
   rc = ensure_stage(d, sizeof(LatRec) * (size_t)std::max<long long>(have, 1));
   if (rc) return rc;
   HIP_TRY(hipMemsetAsync(d->d_cnt, 0, sizeof(unsigned long long), d->last_stream));
-  if (have > 0) {
-    const int blocks = (int)std::min<long long>((have + 255) / 256, 4096);
-    hipLaunchKernelGGL(k_export_lattice, dim3(blocks), dim3(256), 0, d->last_stream, d->dev, channel, have, from_frame,
-                       (LatRec *)d->d_stage, have, d->d_cnt);
+  for (int k = 0; k < 2; ++k) {
+    if (seg_n[k] <= 0) continue;
+    const int blocks = (int)std::min<long long>((seg_n[k] + 255) / 256, 4096);
+    hipLaunchKernelGGL(k_export_lattice, dim3(blocks), dim3(256), 0, d->last_stream, d->dev, channel, seg_lo[k], seg_n[k],
+                       from_frame, (LatRec *)d->d_stage, have, d->d_cnt);
     HIP_TRY(hipGetLastError());
   }
   unsigned long long cnt = 0;
@@ -494,36 +554,51 @@ int wfst_decode_lattice_arcs(wfst_decoder_t *d, int32_t channel, int32_t from_fr
   return 0;
 }
 
-int wfst_decode_lattice_arcs_batch(wfst_decoder_t *d, const int32_t *channels, int32_t n, wfst_lat_arc_t *out,
+static int lattice_arcs_batch_impl(wfst_decoder_t *d, bool snap, const int32_t *channels, int32_t n, wfst_lat_arc_t *out,
                                    int64_t cap, int64_t *offsets, int32_t out_is_device) {
   if (!d || n < 0 || cap < 0 || !offsets || (cap > 0 && !out)) return WFST_E_INVALID_ARG;
   offsets[0] = 0;
   if (n == 0) return 0;
   int rc = check_channels(d, channels, n, true);
   if (rc) return rc;
-  rc = stage_channels(d, channels, n);
+  hipStream_t st = nullptr;
+  rc = readout_stream(d, snap, &st);
   if (rc) return rc;
-  hipStream_t st = d->last_stream;
+  const int sn = snap ? 1 : 0;
+  rc = stage_channels(d, st, channels, n);
+  if (rc) return rc;
   LatRec *dst = (LatRec *)out;
   if (!out_is_device) {                 // host output goes through device staging of the caller's capacity
+    if (sizeof(LatRec) * (size_t)std::max<int64_t>(cap, 1) > d->stage_bytes) HIP_TRY(hipStreamSynchronize(st));
     rc = ensure_stage(d, sizeof(LatRec) * (size_t)std::max<int64_t>(cap, 1));
     if (rc) return rc;
     dst = (LatRec *)d->d_stage;
   }
   // offsets, copy and reset are queued back to back; the copy and the reset check the capacity
   // on the device, so the host waits only once
-  hipLaunchKernelGGL(k_lattice_offsets, dim3(1), dim3(1024), 0, st, d->dev, (const int32_t *)d->d_chans, n, d->d_offs);
+  hipLaunchKernelGGL(k_lattice_offsets, dim3(1), dim3(1024), 0, st, d->dev, (const int32_t *)d->d_chans, n, sn, d->d_offs);
   hipLaunchKernelGGL(k_export_lattice_batch, dim3(n, 8), dim3(256), 0, st, d->dev, (const int32_t *)d->d_chans, n,
                      (const long long *)d->d_offs, dst, (long long)cap);
-  hipLaunchKernelGGL(k_reset_lattice_batch, dim3((n + 255) / 256), dim3(256), 0, st, d->dev, (const int32_t *)d->d_chans, n,
+  hipLaunchKernelGGL(k_reset_lattice_batch, dim3((n + 255) / 256), dim3(256), 0, st, d->dev, (const int32_t *)d->d_chans, n, sn,
                      (const long long *)d->d_offs, (long long)cap);
   HIP_TRY(hipGetLastError());
   static_assert(sizeof(long long) == sizeof(int64_t), "offset width");
-  HIP_TRY(copy_sync(d, offsets, d->d_offs, sizeof(long long) * ((size_t)n + 1), hipMemcpyDeviceToHost));
+  HIP_TRY(copy_sync_on(st, offsets, d->d_offs, sizeof(long long) * ((size_t)n + 1), hipMemcpyDeviceToHost));
+  if (snap) HIP_TRY(hipEventRecord(d->ev_read, st));
   const long long total = offsets[n];
   if (total > cap) return WFST_E_CAPACITY;
-  if (!out_is_device && total > 0) HIP_TRY(copy_sync(d, out, dst, sizeof(LatRec) * (size_t)total, hipMemcpyDeviceToHost));
+  if (!out_is_device && total > 0) HIP_TRY(copy_sync_on(st, out, dst, sizeof(LatRec) * (size_t)total, hipMemcpyDeviceToHost));
   return 0;
+}
+
+int wfst_decode_lattice_arcs_batch(wfst_decoder_t *d, const int32_t *channels, int32_t n, wfst_lat_arc_t *out,
+                                   int64_t cap, int64_t *offsets, int32_t out_is_device) {
+  return lattice_arcs_batch_impl(d, false, channels, n, out, cap, offsets, out_is_device);
+}
+
+int wfst_decode_snapshot_lattice_arcs_batch(wfst_decoder_t *d, const int32_t *channels, int32_t n, wfst_lat_arc_t *out,
+                                            int64_t cap, int64_t *offsets, int32_t out_is_device) {
+  return lattice_arcs_batch_impl(d, true, channels, n, out, cap, offsets, out_is_device);
 }
 
 int wfst_decode_final_lattice(wfst_decoder_t *d, int32_t channel, int32_t use_final, wfst_lat_arc_t *out, int64_t cap,

@@ -72,7 +72,14 @@ struct ChanState {
   int32_t status;            // sticky error code (WFST_E_*) or 0
   int32_t num_frames;        // token frames written (frame 0 comes from init)
   long long hist_used;       // tokens in the history
-  long long lat_count;       // lattice records buffered
+  // Lattice records of a channel live in its region of lat_cap records.  The current epoch
+  // is [lat_start, lat_start + lat_count) and may grow up to lat_limit; a sealed snapshot
+  // that has not been drained yet is [snap_lo, snap_hi) (empty when equal).  Both ranges
+  // are contiguous and disjoint.
+  long long lat_start, lat_count, lat_limit;
+  long long snap_lo, snap_hi;
+  long long snap_hist_used;  // snapshot of hist_used
+  int32_t snap_status, snap_frames;   // snapshot of status and num_frames
   long long lat_total;       // lattice records produced since init
   long long arcs_expanded;
   int32_t max_pre, max_post, closure_iters_max;
@@ -109,6 +116,6 @@ struct DecDev {
 
 // error codes mirrored from the public header (device code cannot include it cleanly)
 constexpr int E_TOKEN_OVERFLOW = -6, E_LATTICE_OVERFLOW = -7, E_DEAD_CHANNEL = -8, E_NAN_INPUT = -9,
-              E_BROKEN_TRACE = -10, E_HISTORY_OVERFLOW = -12, E_CAPACITY = -5;
+              E_BROKEN_TRACE = -10, E_HISTORY_OVERFLOW = -12, E_CAPACITY = -5, E_NOT_INIT = -4;
 
 }  // namespace wfst

@@ -37,15 +37,29 @@ def decode_and_compare(cfg, sample, token_capacity, history_capacity, lattice_ca
     chunk = cfg.chunk or T
     stream = torch.cuda.current_stream().cuda_stream
     lat = {s: [] for s in sample}
+    partial = {s: [] for s in sample}
     base = scores.data_ptr()
-    for f0 in range(0, T, chunk):
+    def launch(f0):
         nfr = np.clip(lens - f0, 0, chunk).astype(np.int32)
         ptrs = (base + (starts[:-1] + np.minimum(f0, lens)) * P * 4).astype(np.uint64)
         dec.advance_ptrs(chans, ptrs, np.full(n_ch, P, np.int32), nfr, stream)
-        if cfg.chunk:                                  # online: every channel is drained after every chunk
-            recs, offs = dec.lattice_arcs_batch(chans)
+
+    launch(0)
+    for f0 in range(0, T, chunk):
+        if cfg.chunk:
+            # online, as the benchmark runs it: the chunk is sealed, the next one is queued, and
+            # every channel is read out from the snapshot while that next chunk decodes
+            dec.snapshot()
+            if f0 + chunk < T:
+                launch(f0 + chunk)
+            paths = dec.best_path_batch(chans, use_final=False, words_cap=1024, raw=True, snapshot=True)
+            assert (paths[4] == 0).all()
+            recs, offs = dec.lattice_arcs_batch(chans, snapshot=True)
             for s in sample:
                 lat[s].append(recs[offs[s]:offs[s + 1]])
+                partial[s].append(paths[0][s, :paths[1][s]].copy())
+        elif f0 + chunk < T:
+            launch(f0 + chunk)
     final_checks = []
     if not cfg.chunk:                                  # offline: one readout per sampled channel at the end
         for s in sample:
@@ -85,6 +99,13 @@ def decode_and_compare(cfg, sample, token_capacity, history_capacity, lattice_ca
                 assert np.array_equal(got["frame"][o2], want["frame"]) and np.array_equal(got["arc"][o2], want["arc"]), label
                 assert np.array_equal(got["extra_cost"][o2].view(np.uint32), want["extra"].view(np.uint32)), label
                 assert np.float32(info["best_cost"]).view(np.uint32) == np.float32(want["best_cost"]).view(np.uint32), label
+        if cfg.chunk:                                  # the per-chunk partial results, against a second checker run
+            od2 = oracle.OracleDecoder(og, cfg.beam, cfg.lattice_beam, cfg.max_active)
+            rows = cfg.loglikes(s, 0, int(lens[s]))
+            for k, f0 in enumerate(range(0, T, chunk)):
+                od2.advance(rows[f0:f0 + chunk])
+                if k % 5 == 0 or f0 + chunk >= T:
+                    assert np.array_equal(partial[s][k], od2.best_path(False)["words"]), f"{label} partial path after chunk {k}"
         for use_final in (True, False):
             bp, gp = od.best_path(use_final), dec.best_path(s, use_final)
             assert np.array_equal(gp["words"], bp["words"]), label

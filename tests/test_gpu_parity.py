@@ -332,3 +332,119 @@ def test_free_and_reuse_channels(torch_cuda, B):
         with pytest.raises(B.WfstError) as e:
             dec.stats(0)
         assert e.value.code == B.WFST_E_NOT_INIT
+
+
+def _oracle_lattice_of_frames(od, lo, hi):
+    """The checker's lattice records with lo <= frame < hi, sorted by (frame, arc)."""
+    fr, ar, ex = od.lattice()
+    m = (fr >= lo) & (fr < hi)
+    return fr[m], ar[m], ex[m]
+
+
+def _assert_records(got, want, label):
+    o = np.lexsort((got["arc"], got["frame"]))
+    fr, ar, ex = want
+    assert len(got) == len(fr), f"{label}: {len(got)} records, expected {len(fr)}"
+    assert np.array_equal(got["frame"][o], fr) and np.array_equal(got["arc"][o], ar), label
+    assert np.array_equal(got["extra_cost"][o].view(np.uint32), ex.view(np.uint32)), label
+
+
+def test_snapshot_readouts_beside_decoding(torch_cuda, B):
+    """Readouts of a sealed snapshot while the next chunk is being decoded (the paper's second
+    stream, Section 3): per-chunk best paths and lattice records must be those of the checker
+    at the snapshot's frame, whatever has been queued behind it.  The lattice buffer is
+    small, so the epochs wrap around the channel's region several times; one channel skips
+    drains, which must delay its records, not lose them."""
+    torch = torch_cuda
+    c = synth.configs()[0]
+    g = synth.make_graph(c.graph)
+    n, T, chunk = 4, 160, 10
+    rows = [c.loglikes(s, 0, T) for s in range(n)]
+    gg = B.WfstGraph(g)
+    dec = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=n, max_lanes=n, max_frames=T,
+                        lattice_capacity=70_000)
+    chans = list(range(n))
+    dec.init_channels(chans)
+    dev = [torch.from_numpy(r).cuda() for r in rows]
+    og = oracle.OracleGraph(g)
+    ods = [oracle.OracleDecoder(og, c.beam, c.lattice_beam, c.max_active) for _ in range(n)]
+    for od, r in zip(ods, rows):
+        od.advance(r)
+    full = [oracle.OracleDecoder(og, c.beam, c.lattice_beam, c.max_active) for _ in range(n)]
+    side = torch.cuda.Stream()
+    nchunks = T // chunk
+    drained_to = [0] * n                       # first frame not yet handed out, per channel
+    sealed_to = [0] * n                        # end of the frames in the channel's undrained snapshot
+    with torch.cuda.stream(side):
+        dec.advance(chans, [d[0:chunk] for d in dev])
+        for k in range(nchunks):
+            end = (k + 1) * chunk + 1          # frames [0, end) exist in the snapshot
+            dec.snapshot()
+            for ch in chans:
+                if sealed_to[ch] == drained_to[ch]:
+                    sealed_to[ch] = end        # the previous snapshot was drained: a new one is taken
+            if k + 1 < nchunks:
+                dec.advance(chans, [d[(k + 1) * chunk:(k + 2) * chunk] for d in dev])
+            for od, r in zip(full, rows):
+                od.advance(r[k * chunk:(k + 1) * chunk])
+            got = dec.best_path_batch(chans, use_final=(k % 2 == 0), snapshot=True)
+            for ch, (r, od) in enumerate(zip(got, full)):
+                want = od.best_path(k % 2 == 0)
+                assert r["status"] == 0
+                assert np.array_equal(r["words"], want["words"]), f"chunk {k} ch {ch}"
+                assert np.float32(r["total_cost"]).view(np.uint32) == np.float32(want["total_cost"]).view(np.uint32)
+            listed = [ch for ch in chans if not (ch == 3 and k % 3 != 2)]   # channel 3 is drained every third chunk
+            recs, offs = dec.lattice_arcs_batch(listed, snapshot=True)
+            for i, ch in enumerate(listed):
+                _assert_records(recs[offs[i]:offs[i + 1]], _oracle_lattice_of_frames(ods[ch], drained_to[ch], sealed_to[ch]),
+                                f"chunk {k} ch {ch}")
+                drained_to[ch] = sealed_to[ch]
+    torch.cuda.synchronize()
+    for ch in chans:
+        assert dec.stats(ch)["status"] == 0
+    # what is left (channel 3: the chunks after its last snapshot) comes out of the live drain
+    recs, offs = dec.lattice_arcs_batch(chans)
+    for ch in chans:
+        _assert_records(recs[offs[ch]:offs[ch + 1]], _oracle_lattice_of_frames(ods[ch], drained_to[ch], T + 1), f"rest ch {ch}")
+    for ch in chans:
+        compare_channel(dec, ch, ods[ch], label=f"snapshot-flow ch{ch}", lattice=False)
+
+
+def test_snapshot_edge_cases(torch_cuda, B):
+    torch = torch_cuda
+    c = synth.configs()[0]
+    g = synth.make_graph(c.graph)
+    gg = B.WfstGraph(g)
+    rows = c.loglikes(0, 0, 40)
+    t = torch.from_numpy(rows).cuda()
+    og = oracle.OracleGraph(g)
+    od = oracle.OracleDecoder(og, c.beam, c.lattice_beam, c.max_active)
+    od.advance(rows)
+    dec = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=2, max_lanes=2, max_frames=40,
+                        lattice_capacity=200_000)
+    dec.init_channels([0, 1])
+    # no snapshot yet
+    with pytest.raises(B.WfstError) as e:
+        dec.best_path_batch([0], snapshot=True)
+    assert e.value.code == B.WFST_E_NOT_INIT
+    dec.advance([0], [t[:20]])
+    dec.snapshot()
+    dec.advance([0], [t[20:40]])
+    # a live drain with an undrained snapshot hands out both, and the final lattice sees the
+    # current epoch only
+    recs = dec.lattice_arcs(0)
+    _assert_records(recs, _oracle_lattice_of_frames(od, 0, 41), "live drain after snapshot")
+    # channel 1 was initialised but never advanced: its snapshot is frame 0
+    r = dec.best_path_batch([1], use_final=False, snapshot=True)[0]
+    assert r["status"] == 0 and len(r["words"]) == 0
+    # an epoch that outgrows the room left beside an undrained snapshot stops the channel cleanly
+    small = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=1, max_lanes=1, max_frames=40,
+                          lattice_capacity=int(len(_oracle_lattice_of_frames(od, 0, 21)[0]) * 1.3))
+    small.init_channels([0])
+    small.advance([0], [t[:20]])
+    small.snapshot()
+    small.advance([0], [t[20:40]])
+    torch.cuda.synchronize()
+    assert small.stats(0)["status"] == B.WFST_E_LATTICE_OVERFLOW
+    recs, offs = small.lattice_arcs_batch([0], snapshot=True)      # the snapshot itself is intact
+    _assert_records(recs, _oracle_lattice_of_frames(od, 0, 21), "snapshot of an overflowed channel")
