@@ -7,10 +7,14 @@ with a best-path and a lattice-arc readout for every channel after every chunk.
 
 A "step" is one pass of the whole hot path over one batch: all 500 lanes advance by one
 50-frame chunk (emitting expansion, closure, pruning, lattice records), and the per-chunk
-readouts of that chunk (best path and lattice arcs of every channel).  The readouts work on
-a snapshot sealed behind the chunk and run beside the next chunk's decoding (the paper's
-second stream, Section 3); --sync-readout makes them wait for each other instead.  Scores
-are generated on the device beforehand and are resident in HBM when the timed region starts.  value = seconds of audio decoded per wall second at
+readouts of that chunk (best path and lattice arcs of every channel).  The lanes are
+persistent workgroups: one advance call covers --chunks-per-call chunks (default: all timed
+ones), every lane seals a snapshot of its channel at each chunk boundary and goes on, and the
+readouts of each boundary run on a second stream beside the decoding (the paper's second
+stream, Section 3) as soon as all lanes have passed it.  Every chunk boundary of every
+channel is read out inside the timed region.  --sync-readout gives the lock-step variant:
+one call per chunk, read out before the next one is queued.  Scores are generated on the
+device beforehand and are resident in HBM when the timed region starts.  value = seconds of audio decoded per wall second at
 10 ms per frame (RTFx), whole job.
 
 Prints ONE JSON line.
@@ -44,7 +48,9 @@ def main() -> int:
     ap.add_argument("--no-readout", action="store_true", help="time the advance calls only")
     ap.add_argument("--cpu-streams", type=int, default=12)
     ap.add_argument("--sync-readout", action="store_true",
-                    help="read each chunk out before the next one is queued (no overlap with decoding)")
+                    help="one call per chunk, read out before the next one is queued (no overlap with decoding)")
+    ap.add_argument("--chunks-per-call", type=int, default=0,
+                    help="chunks one advance call covers (0: all chunks of the warm-up / of the timed region)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 1 GiB device copy (calibrates the HBM byte counters under rocprofv3)")
     args = ap.parse_args()
@@ -87,7 +93,7 @@ def main() -> int:
     torch.cuda.synchronize()
     dec = B.WfstDecoder(graph, cfg.beam, cfg.lattice_beam, cfg.max_active, num_channels=n_ch, max_lanes=n_ch,
                         max_frames=n_frames, token_capacity=16384, history_capacity=2_500_000,
-                        lattice_capacity=400_000)
+                        lattice_capacity=1_000_000)
     ch_np = np.arange(n_ch, dtype=np.int32)
     dec.init_channels(ch_np)
     stream = torch.cuda.Stream().cuda_stream
@@ -98,34 +104,37 @@ def main() -> int:
     readout = not args.no_readout
     overlap = readout and not args.sync_readout
 
-    def launch(i: int):
-        dec.advance_ptrs(ch_np, row0 + np.uint64(i * chunk * P * 4), strides, nfr, stream)
+    def launch(i: int, n_chunks: int = 1, snapshot_every: int = 0):
+        return dec.advance_ptrs(ch_np, row0 + np.uint64(i * chunk * P * 4), strides, nfr * np.int32(n_chunks), stream,
+                                snapshot_every)
 
-    def read():
-        paths = dec.best_path_batch(ch_np, use_final=False, words_cap=1024, raw=True, snapshot=overlap)
-        offs = dec.lattice_arcs_batch(ch_np, out_device=lat_buf, snapshot=overlap)
+    def read(snapshot: int = 0):
+        paths = dec.best_path_batch(ch_np, use_final=False, words_cap=1024, raw=True, snapshot=snapshot)
+        offs = dec.lattice_arcs_batch(ch_np, out_device=lat_buf, snapshot=snapshot)
         return paths, offs
 
     def all_stats():
         return [dec.stats(int(c)) for c in ch_np]
 
     def run(first: int, count: int):
-        """Steps [first, first + count): chunk i is decoded, sealed and read out; with overlap
-        chunk i + 1 is queued before chunk i is read, so it decodes during the readout."""
+        """Steps (chunks) [first, first + count), each decoded and read out."""
         last = None
-        launch(first)
-        for i in range(first, first + count):
-            more = i + 1 < first + count
-            if overlap:
-                dec.snapshot()
-                if more:
-                    launch(i + 1)
-                last = read()
-            else:
+        if not overlap:
+            for i in range(first, first + count):
+                launch(i)
                 if readout:
                     last = read()
-                if more:
-                    launch(i + 1)
+            torch.cuda.synchronize()
+            return last
+        per_call = args.chunks_per_call or count
+        calls = [(i, min(per_call, first + count - i)) for i in range(first, first + count, per_call)]
+        ids = launch(*calls[0], snapshot_every=chunk)
+        for k, (i, m) in enumerate(calls):
+            nxt = launch(*calls[k + 1], snapshot_every=chunk) if k + 1 < len(calls) else None   # queued behind this call
+            assert ids[1] == m
+            for j in range(m):
+                last = read(ids[0] + j)          # waits until all lanes have sealed this boundary
+            ids = nxt
         torch.cuda.synchronize()
         return last
 
@@ -169,8 +178,9 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "configs[3]: 8M-state/23M-arc synthetic graph, %d channels x %d-frame chunks, beam %g, "
                                "max-active %d, lattice-beam %g, per-chunk best-path + lattice readout%s"
-                               % (n_ch, chunk, cfg.beam, cfg.max_active, cfg.lattice_beam, ("" if overlap else " (not overlapped)") if readout else " (readout off)"),
-                   "channels": n_ch, "chunk_frames": chunk, "stream_frames_timed": K * n_ch * chunk},
+                               % (n_ch, chunk, cfg.beam, cfg.max_active, cfg.lattice_beam, ("" if overlap else " (lock-step)") if readout else " (readout off)"),
+                   "channels": n_ch, "chunk_frames": chunk, "stream_frames_timed": K * n_ch * chunk,
+                   "chunks_per_advance_call": (args.chunks_per_call or K) if overlap else 1},
         "arcs_expanded_per_s": round(arcs / wall, 1),
         "stream_frames_per_s": round(K * n_ch * chunk / wall, 1),
         "arcs_per_stream_frame": round(arcs / (K * n_ch * chunk), 1),

@@ -191,40 +191,48 @@ int wfst_decode_lattice_arcs_batch(wfst_decoder_t *decoder, const int32_t *chann
 
 /* Readouts beside the decoding.  The paper hides the per-frame device-to-host token copies
  * behind the next frames' kernels with a second stream (Section 3, Fig. 1); here the tokens
- * stay on the device and it is the per-chunk readouts that run beside the next chunk.
+ * stay on the device and it is the per-chunk readouts that run beside the decoding.
  *
- * wfst_decode_snapshot seals, in stream order behind the advance calls queued so far, the
- * state of EVERY channel of the decoder: its status and frame count, and the lattice arcs
- * buffered since the last drain, which become the channel's snapshot and leave the buffer
- * that later frames append to.  A channel whose previous snapshot has not been drained
- * keeps that snapshot; its newer arcs stay buffered for a later one (nothing is lost).
- * The call itself does not wait for the device.
+ * wfst_decode_advance_snapshots is wfst_decode_advance with one addition: after every
+ * snapshot_every (>= 1) frames of the call each lane seals a snapshot of its channel - its
+ * status and frame count, and how many lattice arcs it had produced - and goes on decoding.
+ * The call seals *n_snapshots = max(1, ceil(longest n_frames / snapshot_every)) snapshots
+ * (at most 256) with consecutive ids starting at *first_id (ids are positive and grow over
+ * the decoder's life); a lane with fewer frames, or one that stops with an error, seals the
+ * remaining ones in the state it ends in.  Lanes do not wait for each other at the
+ * boundaries, so one call over many chunks keeps the whole GPU busy although the chunks
+ * differ from lane to lane; a channel keeps its last 256 snapshots.
  *
- * The two readouts below do what wfst_decode_best_path_batch and
- * wfst_decode_lattice_arcs_batch do, but on the snapshot: best paths end at the snapshot's
- * last frame, the lattice readout hands out and drains the snapshot's arcs only.  They run
- * on a stream of the decoder's own, wait for the snapshot (not for advance calls queued
- * after it) and synchronise with that stream alone, so an advance call queued after the
- * snapshot decodes while they run.  A channel without a snapshot reports WFST_E_NOT_INIT
- * in status[i] / contributes no arcs; the functions return WFST_E_NOT_INIT if no snapshot
- * was ever taken.  Take the next snapshot only after the readouts of the previous one have
- * returned.  While advance calls are in flight use only these two readouts; every other
- * readout of this header refers to the live state and waits for the decoding.  A DEVICE
- * output buffer is written on the decoder's own stream: it is complete when the call
- * returns.  The capacity left to a channel's arcs between two drains is at least half of
- * lattice_capacity minus one snapshot. */
-int wfst_decode_snapshot(wfst_decoder_t *decoder);
-int wfst_decode_snapshot_best_path_batch(wfst_decoder_t *decoder, const int32_t *channels,
-                                         int32_t n, int32_t use_final, int32_t *words,
-                                         int32_t words_cap, int32_t *n_words, float *total_cost,
-                                         int32_t *reached_final, int32_t *status);
-int wfst_decode_snapshot_lattice_arcs_batch(wfst_decoder_t *decoder, const int32_t *channels,
-                                            int32_t n, wfst_lat_arc_t *out, int64_t cap,
-                                            int64_t *offsets, int32_t out_is_device);
+ * wfst_decode_snapshot_wait blocks the calling host thread until every lane of the call has
+ * sealed snapshot `id` (WFST_E_NOT_INIT for an id no recent call has produced).  The two
+ * readouts below wait likewise and then do what wfst_decode_best_path_batch and
+ * wfst_decode_lattice_arcs_batch do, on the snapshot: best paths end at the snapshot's last
+ * frame; the lattice readout hands out and drains the arcs not handed out before, up to the
+ * snapshot (so snapshots read in order give each chunk's arcs, and a skipped one is not
+ * lost).  They run on a stream of the decoder's own and synchronise with that stream alone,
+ * so the lanes go on decoding while they run.  A listed channel without that snapshot
+ * reports WFST_E_NOT_INIT in status[i] / contributes no arcs.  While an advance call is in
+ * flight use only these readouts on its channels; every other readout of this header refers
+ * to the live state and waits for the decoding.  A DEVICE output buffer is written on the
+ * decoder's own stream and is complete when the call returns.  Lattice arcs that have not
+ * been handed out occupy the channel's lattice_capacity; arcs drained beside a running call
+ * free their space for that same call. */
+int wfst_decode_advance_snapshots(wfst_decoder_t *decoder, const int32_t *channels, int32_t n_lanes,
+                                  const float *const *loglikes, const int32_t *strides,
+                                  const int32_t *n_frames, int32_t snapshot_every, void *stream,
+                                  int64_t *first_id, int32_t *n_snapshots);
+int wfst_decode_snapshot_wait(wfst_decoder_t *decoder, int64_t id);
+int wfst_decode_snapshot_best_path_batch(wfst_decoder_t *decoder, int64_t snapshot_id,
+                                         const int32_t *channels, int32_t n, int32_t use_final,
+                                         int32_t *words, int32_t words_cap, int32_t *n_words,
+                                         float *total_cost, int32_t *reached_final, int32_t *status);
+int wfst_decode_snapshot_lattice_arcs_batch(wfst_decoder_t *decoder, int64_t snapshot_id,
+                                            const int32_t *channels, int32_t n, wfst_lat_arc_t *out,
+                                            int64_t cap, int64_t *offsets, int32_t out_is_device);
 
 /* Final lattice of a channel (the step the paper leaves to the end of the utterance, Section
  * 3.4): backward pruning, with the lattice beam, of the lattice arcs currently buffered for
- * the channel (all arcs since its last drain or snapshot; nothing is drained).  Every token gets an extra
+ * the channel (all arcs not handed out yet; nothing is drained).  Every token gets an extra
  * cost te = min over buffered arcs leaving it of (te of the arc's destination + the arc's
  * extra cost); in the last frame te is the token's cost (+ final cost, over final states, if
  * use_final and one holds a token) minus the best such cost.  An arc is kept iff te of its

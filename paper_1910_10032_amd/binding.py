@@ -24,8 +24,8 @@ EXPORTS = [
     "wfst_decode_graph_load", "wfst_decode_graph_free", "wfst_decode_graph_bytes", "wfst_decode_create",
     "wfst_decode_destroy", "wfst_decode_state_bytes", "wfst_decode_init_channels", "wfst_decode_free_channels",
     "wfst_decode_advance", "wfst_decode_best_path_batch", "wfst_decode_best_path", "wfst_decode_best_path_arcs",
-    "wfst_decode_lattice_arcs", "wfst_decode_lattice_arcs_batch", "wfst_decode_snapshot",
-    "wfst_decode_snapshot_best_path_batch", "wfst_decode_snapshot_lattice_arcs_batch", "wfst_decode_final_lattice", "wfst_decode_tokens", "wfst_decode_stats", "wfst_decode_set_profiling",
+    "wfst_decode_lattice_arcs", "wfst_decode_lattice_arcs_batch", "wfst_decode_advance_snapshots",
+    "wfst_decode_snapshot_wait", "wfst_decode_snapshot_best_path_batch", "wfst_decode_snapshot_lattice_arcs_batch", "wfst_decode_final_lattice", "wfst_decode_tokens", "wfst_decode_stats", "wfst_decode_set_profiling",
     "wfst_decode_profile", "wfst_decode_strerror",
 ]
 
@@ -86,9 +86,10 @@ def lib():
         L.wfst_decode_best_path_arcs.argtypes = [vp, i32, i32, vp, i32, C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(i32)]
         L.wfst_decode_lattice_arcs.argtypes = [vp, i32, i32, vp, i64, C.POINTER(i64), i32]
         L.wfst_decode_lattice_arcs_batch.argtypes = [vp, vp, i32, vp, i64, vp, i32]
-        L.wfst_decode_snapshot.argtypes = [vp]
-        L.wfst_decode_snapshot_best_path_batch.argtypes = L.wfst_decode_best_path_batch.argtypes
-        L.wfst_decode_snapshot_lattice_arcs_batch.argtypes = L.wfst_decode_lattice_arcs_batch.argtypes
+        L.wfst_decode_advance_snapshots.argtypes = [vp, vp, i32, vp, vp, vp, i32, vp, C.POINTER(i64), C.POINTER(i32)]
+        L.wfst_decode_snapshot_wait.argtypes = [vp, i64]
+        L.wfst_decode_snapshot_best_path_batch.argtypes = [vp, i64, vp, i32, i32, vp, i32, vp, vp, vp, vp]
+        L.wfst_decode_snapshot_lattice_arcs_batch.argtypes = [vp, i64, vp, i32, vp, i64, vp, i32]
         L.wfst_decode_final_lattice.argtypes = [vp, i32, i32, vp, i64, C.POINTER(i64), i32, C.POINTER(wfst_lattice_info_t)]
         L.wfst_decode_tokens.argtypes = [vp, i32, i32, vp, i32, C.POINTER(i32)]
         L.wfst_decode_stats.argtypes = [vp, i32, C.POINTER(wfst_stats_t)]
@@ -177,9 +178,10 @@ class WfstDecoder:
         ch = np.ascontiguousarray(channels, np.int32)
         _check(lib().wfst_decode_free_channels(self.h, ch.ctypes.data, len(ch)), "wfst_decode_free_channels")
 
-    def advance(self, channels, loglikes, n_frames=None, stream=None) -> None:
+    def advance(self, channels, loglikes, n_frames=None, stream=None, snapshot_every: int = 0):
         """loglikes: one 2-D float32 cuda tensor per lane (rows = frames), or a list of
-        (device_ptr, stride) pairs together with n_frames."""
+        (device_ptr, stride) pairs together with n_frames.  With snapshot_every > 0 the lanes seal
+        a snapshot after every that many frames; returns (first snapshot id, number of snapshots)."""
         ch = np.ascontiguousarray(channels, np.int32)
         n = len(ch)
         ptrs = np.empty(n, np.uint64)
@@ -196,27 +198,38 @@ class WfstDecoder:
         if stream is None:
             import torch
             stream = torch.cuda.current_stream().cuda_stream
-        _check(lib().wfst_decode_advance(self.h, ch.ctypes.data, n, ptrs.ctypes.data, strides.ctypes.data,
-                                         nfr.ctypes.data, C.c_void_p(stream)), "wfst_decode_advance")
+        return self.advance_ptrs(ch, ptrs, strides, nfr, stream, snapshot_every)
 
     def advance_ptrs(self, channels: np.ndarray, ptrs: np.ndarray, strides: np.ndarray, n_frames: np.ndarray,
-                     stream: int) -> None:
-        """wfst_decode_advance with ready-made argument arrays (int32 / uint64 / int32 / int32)."""
-        _check(lib().wfst_decode_advance(self.h, channels.ctypes.data, len(channels), ptrs.ctypes.data,
-                                         strides.ctypes.data, n_frames.ctypes.data, C.c_void_p(stream)),
-               "wfst_decode_advance")
+                     stream: int, snapshot_every: int = 0):
+        """wfst_decode_advance(_snapshots) with ready-made argument arrays (int32 / uint64 / int32 / int32)."""
+        if snapshot_every <= 0:
+            _check(lib().wfst_decode_advance(self.h, channels.ctypes.data, len(channels), ptrs.ctypes.data,
+                                             strides.ctypes.data, n_frames.ctypes.data, C.c_void_p(stream)),
+                   "wfst_decode_advance")
+            return None
+        first, count = C.c_int64(), C.c_int32()
+        _check(lib().wfst_decode_advance_snapshots(self.h, channels.ctypes.data, len(channels), ptrs.ctypes.data,
+                                                   strides.ctypes.data, n_frames.ctypes.data, snapshot_every,
+                                                   C.c_void_p(stream), C.byref(first), C.byref(count)),
+               "wfst_decode_advance_snapshots")
+        return first.value, count.value
 
-    def snapshot(self):
-        _check(lib().wfst_decode_snapshot(self.h), "wfst_decode_snapshot")
+    def snapshot_wait(self, snapshot_id: int) -> None:
+        _check(lib().wfst_decode_snapshot_wait(self.h, snapshot_id), "wfst_decode_snapshot_wait")
 
     def best_path_batch(self, channels, use_final: bool = True, words_cap: int = 4096, raw: bool = False,
-                        snapshot: bool = False):
+                        snapshot: int = 0):
         """Per channel: dict(status, words, total_cost, reached_final); with raw=True the
         arrays (words [n, cap], n_words, total_cost, reached_final, status) as filled by the call.
-        snapshot=True reads the state sealed by the last snapshot() call."""
+        snapshot = id of a sealed snapshot to read instead of the live state."""
         ch = np.ascontiguousarray(channels, np.int32)
         n = len(ch)
-        fn = lib().wfst_decode_snapshot_best_path_batch if snapshot else lib().wfst_decode_best_path_batch
+        if snapshot:
+            def fn(h, *a):
+                return lib().wfst_decode_snapshot_best_path_batch(h, snapshot, *a)
+        else:
+            fn = lib().wfst_decode_best_path_batch
         if raw:
             words = np.empty((n, max(words_cap, 1)), np.int32)
             nw, tc = np.empty(n, np.int32), np.empty(n, np.float32)
@@ -278,11 +291,15 @@ class WfstDecoder:
             _check(rc, "wfst_decode_lattice_arcs")
             return out[:n.value].copy()
 
-    def lattice_arcs_batch(self, channels, cap: int = 1 << 20, out_device=None, snapshot: bool = False):
+    def lattice_arcs_batch(self, channels, cap: int = 1 << 20, out_device=None, snapshot: int = 0):
         """Drains several channels: (records, offsets) on the host, or offsets only when the
-        records go into the cuda tensor `out_device`.  snapshot=True drains the arcs sealed by
-        the last snapshot() call."""
-        fn = lib().wfst_decode_snapshot_lattice_arcs_batch if snapshot else lib().wfst_decode_lattice_arcs_batch
+        records go into the cuda tensor `out_device`.  snapshot = id of a sealed snapshot up to
+        which the arcs are drained, instead of the live state."""
+        if snapshot:
+            def fn(h, *a):
+                return lib().wfst_decode_snapshot_lattice_arcs_batch(h, snapshot, *a)
+        else:
+            fn = lib().wfst_decode_lattice_arcs_batch
         ch = np.ascontiguousarray(channels, np.int32)
         offs = np.zeros(len(ch) + 1, np.int64)
         while True:

@@ -8,6 +8,8 @@
 #include <cstdint>
 #include <cstring>
 #include <new>
+#include <deque>
+#include <thread>
 #include <vector>
 
 #include "../../include/wfst_decode.h"
@@ -55,9 +57,10 @@ struct wfst_decoder {
   long long *d_offs = nullptr;          // readout scratch [max(num_channels, max_lanes) + 1]
   hipStream_t last_stream = nullptr;    // stream of the last advance call; readouts use it
   hipStream_t side_stream = nullptr;    // snapshot readouts run here, beside the decoding
-  hipEvent_t ev_snap = nullptr;         // the last snapshot has been taken
-  hipEvent_t ev_read = nullptr;         // the last snapshot readout has finished
-  bool have_snapshot = false;
+  long long *h_sealed = nullptr;        // pinned [max_lanes]: id of the last snapshot each lane sealed
+  int64_t next_snap_id = 1;
+  struct SnapCall { int64_t id0; int32_t n_snaps, n_lanes; hipStream_t stream; };
+  std::deque<SnapCall> snap_calls;      // the advance calls that seal snapshots, newest last
   bool profiling = false;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
 };
@@ -256,6 +259,7 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
   const size_t nc = (size_t)c.num_channels, nl = (size_t)c.max_lanes;
   int rc = 0;
   if (!rc) rc = dev_alloc(d, &D.chan, nc);
+  if (!rc) rc = dev_alloc(d, &D.snap, nc * (size_t)SNAP_RING);
   if (!rc) rc = dev_alloc(d, &D.frame_off, nc * (size_t)(c.max_frames + 2));
   if (!rc) rc = dev_alloc(d, &D.hist, nc * (size_t)D.hist_cap);
   if (!rc) rc = dev_alloc(d, &D.lat, nc * (size_t)D.lat_cap);
@@ -285,9 +289,13 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
     for (int i = 0; ok && i < PARAM_RING; ++i)
       ok = hipHostMalloc((void **)&d->h_params[i], sizeof(LaneParam) * nl) == hipSuccess &&
            hipEventCreateWithFlags(&d->param_ev[i], hipEventDisableTiming) == hipSuccess;
-    ok = ok && hipStreamCreateWithFlags(&d->side_stream, hipStreamNonBlocking) == hipSuccess &&
-         hipEventCreateWithFlags(&d->ev_snap, hipEventDisableTiming) == hipSuccess &&
-         hipEventCreateWithFlags(&d->ev_read, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipMemset(D.snap, 0, sizeof(ChanSnap) * nc * SNAP_RING) == hipSuccess &&
+         hipStreamCreateWithFlags(&d->side_stream, hipStreamNonBlocking) == hipSuccess &&
+         hipHostMalloc((void **)&d->h_sealed, sizeof(long long) * nl) == hipSuccess;
+    if (ok) {
+      std::memset(d->h_sealed, 0, sizeof(long long) * nl);
+      ok = hipHostGetDevicePointer((void **)&D.lane_sealed, d->h_sealed, 0) == hipSuccess;
+    }
     if (ok) {
       hipLaunchKernelGGL(k_fill_slots, dim3(1024), dim3(256), 0, 0, D.slots, nl * (size_t)D.H);
       ok = hipGetLastError() == hipSuccess && hipDeviceSynchronize() == hipSuccess;
@@ -311,9 +319,8 @@ void wfst_decode_destroy(wfst_decoder_t *d) {
     if (d->param_ev[i]) (void)hipEventDestroy(d->param_ev[i]);
   }
   for (auto &p : d->prof_events) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
-  if (d->ev_snap) (void)hipEventDestroy(d->ev_snap);
-  if (d->ev_read) (void)hipEventDestroy(d->ev_read);
   if (d->side_stream) (void)hipStreamDestroy(d->side_stream);
+  if (d->h_sealed) (void)hipHostFree(d->h_sealed);
   delete d;
 }
 
@@ -335,7 +342,7 @@ int wfst_decode_init_channels(wfst_decoder_t *d, const int32_t *channels, int32_
   for (int32_t i = 0; i < n; i += d->cfg.max_lanes) {
     const int32_t m = std::min(d->cfg.max_lanes, n - i);
     lp.clear();
-    for (int32_t k = 0; k < m; ++k) lp.push_back(LaneParam{nullptr, channels[i + k], 1, 0, 0});
+    for (int32_t k = 0; k < m; ++k) lp.push_back(LaneParam{nullptr, channels[i + k], 1, 0, 0, 0, 0, 0});
     rc = launch_lanes(d, lp, 1, nullptr);
     if (rc) return rc;
   }
@@ -352,9 +359,12 @@ int wfst_decode_free_channels(wfst_decoder_t *d, const int32_t *channels, int32_
   return 0;
 }
 
-int wfst_decode_advance(wfst_decoder_t *d, const int32_t *channels, int32_t n_lanes, const float *const *loglikes,
-                        const int32_t *strides, const int32_t *n_frames, void *stream) {
-  if (!d || n_lanes < 0 || n_lanes > d->cfg.max_lanes) return WFST_E_INVALID_ARG;
+static int advance_impl(wfst_decoder_t *d, const int32_t *channels, int32_t n_lanes, const float *const *loglikes,
+                        const int32_t *strides, const int32_t *n_frames, int32_t snapshot_every, void *stream,
+                        int64_t *first_id, int32_t *n_snapshots) {
+  if (!d || n_lanes < 0 || n_lanes > d->cfg.max_lanes || snapshot_every < 0) return WFST_E_INVALID_ARG;
+  if (first_id) *first_id = 0;
+  if (n_snapshots) *n_snapshots = 0;
   if (n_lanes == 0) return 0;
   if (!loglikes || !strides || !n_frames) return WFST_E_INVALID_ARG;
   int rc = check_channels(d, channels, n_lanes, true);
@@ -364,14 +374,68 @@ int wfst_decode_advance(wfst_decoder_t *d, const int32_t *channels, int32_t n_la
     if (n_frames[i] > 0 && !loglikes[i]) return WFST_E_INVALID_ARG;
     if (d->frames_fed[channels[i]] + n_frames[i] > d->cfg.max_frames) return WFST_E_HISTORY_OVERFLOW;
   }
+  // snapshots of the call: one per snapshot_every frames of its longest lane, at least one
+  int32_t n_snaps = 0;
+  if (snapshot_every > 0) {
+    int32_t longest = 0;
+    for (int32_t i = 0; i < n_lanes; ++i) longest = std::max(longest, n_frames[i]);
+    n_snaps = std::max(1, (longest + snapshot_every - 1) / snapshot_every);
+    if (n_snaps > SNAP_RING) return WFST_E_INVALID_ARG;
+  }
+  const int64_t id0 = d->next_snap_id;
   std::vector<LaneParam> lp((size_t)n_lanes);
   for (int32_t i = 0; i < n_lanes; ++i) {
-    lp[i] = LaneParam{loglikes[i], channels[i], n_frames[i], strides[i], 0};
+    lp[i] = LaneParam{loglikes[i], channels[i], n_frames[i], strides[i], snapshot_every, id0, n_snaps, 0};
     d->frames_fed[channels[i]] += n_frames[i];
   }
   d->last_stream = (hipStream_t)stream;
-  return launch_lanes(d, lp, 0, (hipStream_t)stream);
+  rc = launch_lanes(d, lp, 0, (hipStream_t)stream);
+  if (rc) return rc;
+  if (n_snaps > 0) {
+    d->next_snap_id += n_snaps;
+    d->snap_calls.push_back({id0, n_snaps, n_lanes, (hipStream_t)stream});
+    if (d->snap_calls.size() > 64) d->snap_calls.pop_front();
+    if (first_id) *first_id = id0;
+    if (n_snapshots) *n_snapshots = n_snaps;
+  }
+  return 0;
 }
+
+int wfst_decode_advance(wfst_decoder_t *d, const int32_t *channels, int32_t n_lanes, const float *const *loglikes,
+                        const int32_t *strides, const int32_t *n_frames, void *stream) {
+  return advance_impl(d, channels, n_lanes, loglikes, strides, n_frames, 0, stream, nullptr, nullptr);
+}
+
+int wfst_decode_advance_snapshots(wfst_decoder_t *d, const int32_t *channels, int32_t n_lanes, const float *const *loglikes,
+                                  const int32_t *strides, const int32_t *n_frames, int32_t snapshot_every, void *stream,
+                                  int64_t *first_id, int32_t *n_snapshots) {
+  if (snapshot_every < 1 || !first_id || !n_snapshots) return WFST_E_INVALID_ARG;
+  return advance_impl(d, channels, n_lanes, loglikes, strides, n_frames, snapshot_every, stream, first_id, n_snapshots);
+}
+
+// Wait on the host until every lane of the call that seals snapshot `id` has sealed it.  The
+// lanes publish their progress in pinned host memory; the kernel never waits for anybody, so
+// this cannot stall the device.  If the call's stream has drained and the snapshot is still
+// missing, something went wrong on the device.
+int wfst_decode_snapshot_wait(wfst_decoder_t *d, int64_t id) {
+  if (!d || id < 1) return WFST_E_INVALID_ARG;
+  const wfst_decoder::SnapCall *call = nullptr;
+  for (const auto &c : d->snap_calls) if (id >= c.id0 && id < c.id0 + c.n_snaps) call = &c;
+  if (!call) return WFST_E_NOT_INIT;
+  bool stream_done = false;
+  for (;;) {
+    bool all = true;
+    for (int32_t i = 0; i < call->n_lanes && all; ++i)
+      all = __atomic_load_n(&d->h_sealed[i], __ATOMIC_ACQUIRE) >= id;
+    if (all) return 0;
+    if (stream_done) return WFST_E_DEVICE;
+    const hipError_t q = hipStreamQuery(call->stream);
+    if (q == hipSuccess) stream_done = true;            // look at the progress words once more, then give up
+    else if (q != hipErrorNotReady) { (void)hipGetLastError(); return WFST_E_DEVICE; }
+    else std::this_thread::yield();
+  }
+}
+
 
 // Readouts run on the stream of the decoder's last advance call and wait for that stream
 // only, so decoders working on different streams do not wait for each other.
@@ -384,12 +448,12 @@ static hipError_t copy_sync(wfst_decoder *d, void *dst, const void *src, size_t 
   return copy_sync_on(d->last_stream, dst, src, bytes, kind);
 }
 
-// Stream a readout runs on.  A snapshot readout runs on the decoder's side stream once the
-// snapshot has been taken; it does not wait for decoding queued after the snapshot.
-static int readout_stream(wfst_decoder *d, bool snap, hipStream_t *st) {
-  if (!snap) { *st = d->last_stream; return 0; }
-  if (!d->have_snapshot) return WFST_E_NOT_INIT;
-  HIP_TRY(hipStreamWaitEvent(d->side_stream, d->ev_snap, 0));
+// Stream a readout runs on.  A snapshot readout runs on the decoder's side stream once all
+// lanes have sealed the snapshot; it does not wait for the decoding that goes on behind it.
+static int readout_stream(wfst_decoder *d, int64_t snap_id, hipStream_t *st) {
+  if (snap_id <= 0) { *st = d->last_stream; return 0; }
+  const int rc = wfst_decode_snapshot_wait(d, snap_id);
+  if (rc) return rc;
   *st = d->side_stream;
   return 0;
 }
@@ -402,7 +466,7 @@ static int stage_channels(wfst_decoder *d, hipStream_t st, const int32_t *channe
   return 0;
 }
 
-static int best_path_batch_impl(wfst_decoder_t *d, bool snap, const int32_t *channels, int32_t n, int32_t use_final,
+static int best_path_batch_impl(wfst_decoder_t *d, int64_t snap, const int32_t *channels, int32_t n, int32_t use_final,
                                 int32_t *words, int32_t words_cap, int32_t *n_words, float *total_cost,
                                 int32_t *reached_final, int32_t *status) {
   if (!d || n < 0 || words_cap < 0 || (n > 0 && (!n_words || !total_cost || !reached_final || !status))) return WFST_E_INVALID_ARG;
@@ -413,7 +477,7 @@ static int best_path_batch_impl(wfst_decoder_t *d, bool snap, const int32_t *cha
   hipStream_t st = nullptr;
   rc = readout_stream(d, snap, &st);
   if (rc) return rc;
-  const int sn = snap ? 1 : 0;
+  const long long sn = snap > 0 ? (long long)snap : 0ll;
   if (sizeof(int32_t) * (size_t)n * (size_t)std::max(words_cap, 1) > d->stage_bytes) {
     HIP_TRY(hipStreamSynchronize(st));            // the staging buffer is about to be replaced
     rc = ensure_stage(d, sizeof(int32_t) * (size_t)n * (size_t)std::max(words_cap, 1));
@@ -449,35 +513,21 @@ static int best_path_batch_impl(wfst_decoder_t *d, bool snap, const int32_t *cha
     }
     status[i] = po[i].status; n_words[i] = po[i].n_words; total_cost[i] = po[i].total_cost; reached_final[i] = po[i].reached_final;
   }
-  if (snap) HIP_TRY(hipEventRecord(d->ev_read, st));
   return 0;
 }
 
 int wfst_decode_best_path_batch(wfst_decoder_t *d, const int32_t *channels, int32_t n, int32_t use_final,
                                 int32_t *words, int32_t words_cap, int32_t *n_words, float *total_cost,
                                 int32_t *reached_final, int32_t *status) {
-  return best_path_batch_impl(d, false, channels, n, use_final, words, words_cap, n_words, total_cost, reached_final, status);
+  return best_path_batch_impl(d, 0, channels, n, use_final, words, words_cap, n_words, total_cost, reached_final, status);
 }
 
-int wfst_decode_snapshot_best_path_batch(wfst_decoder_t *d, const int32_t *channels, int32_t n, int32_t use_final,
-                                         int32_t *words, int32_t words_cap, int32_t *n_words, float *total_cost,
-                                         int32_t *reached_final, int32_t *status) {
-  return best_path_batch_impl(d, true, channels, n, use_final, words, words_cap, n_words, total_cost, reached_final, status);
+int wfst_decode_snapshot_best_path_batch(wfst_decoder_t *d, int64_t snapshot_id, const int32_t *channels, int32_t n,
+                                         int32_t use_final, int32_t *words, int32_t words_cap, int32_t *n_words,
+                                         float *total_cost, int32_t *reached_final, int32_t *status) {
+  if (snapshot_id < 1) return WFST_E_INVALID_ARG;
+  return best_path_batch_impl(d, snapshot_id, channels, n, use_final, words, words_cap, n_words, total_cost, reached_final, status);
 }
-
-int wfst_decode_snapshot(wfst_decoder_t *d) {
-  if (!d) return WFST_E_INVALID_ARG;
-  // the previous snapshot's readouts must be over before its fields are replaced
-  HIP_TRY(hipStreamWaitEvent(d->last_stream, d->ev_read, 0));
-  const int nc = d->cfg.num_channels;
-  hipLaunchKernelGGL(k_snapshot, dim3((nc + 255) / 256), dim3(256), 0, d->last_stream, d->dev, nc);
-  HIP_TRY(hipGetLastError());
-  HIP_TRY(hipEventRecord(d->ev_snap, d->last_stream));
-  d->have_snapshot = true;
-  return 0;
-}
-
-
 
 int wfst_decode_best_path(wfst_decoder_t *d, int32_t channel, int32_t use_final, int32_t *words, int32_t cap,
                           int32_t *n_words, float *total_cost, int32_t *reached_final) {
@@ -529,17 +579,14 @@ int wfst_decode_lattice_arcs(wfst_decoder_t *d, int32_t channel, int32_t from_fr
   rc = read_chan(d, channel, &cs);
   if (rc) return rc;
   if (cs.status != 0 && cs.status != WFST_E_DEAD_CHANNEL && cs.status != WFST_E_NAN_INPUT) return cs.status;
-  // an undrained snapshot first, then the current epoch
-  const long long seg_lo[2] = {cs.snap_lo, cs.lat_start}, seg_n[2] = {cs.snap_hi - cs.snap_lo, cs.lat_count};
-  const long long have = seg_n[0] + seg_n[1];
+  const long long have = cs.lat_total - cs.lat_head;
   rc = ensure_stage(d, sizeof(LatRec) * (size_t)std::max<long long>(have, 1));
   if (rc) return rc;
   HIP_TRY(hipMemsetAsync(d->d_cnt, 0, sizeof(unsigned long long), d->last_stream));
-  for (int k = 0; k < 2; ++k) {
-    if (seg_n[k] <= 0) continue;
-    const int blocks = (int)std::min<long long>((seg_n[k] + 255) / 256, 4096);
-    hipLaunchKernelGGL(k_export_lattice, dim3(blocks), dim3(256), 0, d->last_stream, d->dev, channel, seg_lo[k], seg_n[k],
-                       from_frame, (LatRec *)d->d_stage, have, d->d_cnt);
+  if (have > 0) {
+    const int blocks = (int)std::min<long long>((have + 255) / 256, 4096);
+    hipLaunchKernelGGL(k_export_lattice, dim3(blocks), dim3(256), 0, d->last_stream, d->dev, channel,
+                       cs.lat_head % d->dev.lat_cap, have, from_frame, (LatRec *)d->d_stage, have, d->d_cnt);
     HIP_TRY(hipGetLastError());
   }
   unsigned long long cnt = 0;
@@ -554,7 +601,7 @@ int wfst_decode_lattice_arcs(wfst_decoder_t *d, int32_t channel, int32_t from_fr
   return 0;
 }
 
-static int lattice_arcs_batch_impl(wfst_decoder_t *d, bool snap, const int32_t *channels, int32_t n, wfst_lat_arc_t *out,
+static int lattice_arcs_batch_impl(wfst_decoder_t *d, int64_t snap, const int32_t *channels, int32_t n, wfst_lat_arc_t *out,
                                    int64_t cap, int64_t *offsets, int32_t out_is_device) {
   if (!d || n < 0 || cap < 0 || !offsets || (cap > 0 && !out)) return WFST_E_INVALID_ARG;
   offsets[0] = 0;
@@ -564,7 +611,7 @@ static int lattice_arcs_batch_impl(wfst_decoder_t *d, bool snap, const int32_t *
   hipStream_t st = nullptr;
   rc = readout_stream(d, snap, &st);
   if (rc) return rc;
-  const int sn = snap ? 1 : 0;
+  const long long sn = snap > 0 ? (long long)snap : 0ll;
   rc = stage_channels(d, st, channels, n);
   if (rc) return rc;
   LatRec *dst = (LatRec *)out;
@@ -579,12 +626,11 @@ static int lattice_arcs_batch_impl(wfst_decoder_t *d, bool snap, const int32_t *
   hipLaunchKernelGGL(k_lattice_offsets, dim3(1), dim3(1024), 0, st, d->dev, (const int32_t *)d->d_chans, n, sn, d->d_offs);
   hipLaunchKernelGGL(k_export_lattice_batch, dim3(n, 8), dim3(256), 0, st, d->dev, (const int32_t *)d->d_chans, n,
                      (const long long *)d->d_offs, dst, (long long)cap);
-  hipLaunchKernelGGL(k_reset_lattice_batch, dim3((n + 255) / 256), dim3(256), 0, st, d->dev, (const int32_t *)d->d_chans, n, sn,
+  hipLaunchKernelGGL(k_reset_lattice_batch, dim3((n + 255) / 256), dim3(256), 0, st, d->dev, (const int32_t *)d->d_chans, n,
                      (const long long *)d->d_offs, (long long)cap);
   HIP_TRY(hipGetLastError());
   static_assert(sizeof(long long) == sizeof(int64_t), "offset width");
   HIP_TRY(copy_sync_on(st, offsets, d->d_offs, sizeof(long long) * ((size_t)n + 1), hipMemcpyDeviceToHost));
-  if (snap) HIP_TRY(hipEventRecord(d->ev_read, st));
   const long long total = offsets[n];
   if (total > cap) return WFST_E_CAPACITY;
   if (!out_is_device && total > 0) HIP_TRY(copy_sync_on(st, out, dst, sizeof(LatRec) * (size_t)total, hipMemcpyDeviceToHost));
@@ -593,12 +639,13 @@ static int lattice_arcs_batch_impl(wfst_decoder_t *d, bool snap, const int32_t *
 
 int wfst_decode_lattice_arcs_batch(wfst_decoder_t *d, const int32_t *channels, int32_t n, wfst_lat_arc_t *out,
                                    int64_t cap, int64_t *offsets, int32_t out_is_device) {
-  return lattice_arcs_batch_impl(d, false, channels, n, out, cap, offsets, out_is_device);
+  return lattice_arcs_batch_impl(d, 0, channels, n, out, cap, offsets, out_is_device);
 }
 
-int wfst_decode_snapshot_lattice_arcs_batch(wfst_decoder_t *d, const int32_t *channels, int32_t n, wfst_lat_arc_t *out,
-                                            int64_t cap, int64_t *offsets, int32_t out_is_device) {
-  return lattice_arcs_batch_impl(d, true, channels, n, out, cap, offsets, out_is_device);
+int wfst_decode_snapshot_lattice_arcs_batch(wfst_decoder_t *d, int64_t snapshot_id, const int32_t *channels, int32_t n,
+                                            wfst_lat_arc_t *out, int64_t cap, int64_t *offsets, int32_t out_is_device) {
+  if (snapshot_id < 1) return WFST_E_INVALID_ARG;
+  return lattice_arcs_batch_impl(d, snapshot_id, channels, n, out, cap, offsets, out_is_device);
 }
 
 int wfst_decode_final_lattice(wfst_decoder_t *d, int32_t channel, int32_t use_final, wfst_lat_arc_t *out, int64_t cap,

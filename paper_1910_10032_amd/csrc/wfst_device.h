@@ -72,28 +72,40 @@ struct ChanState {
   int32_t status;            // sticky error code (WFST_E_*) or 0
   int32_t num_frames;        // token frames written (frame 0 comes from init)
   long long hist_used;       // tokens in the history
-  // Lattice records of a channel live in its region of lat_cap records.  The current epoch
-  // is [lat_start, lat_start + lat_count) and may grow up to lat_limit; a sealed snapshot
-  // that has not been drained yet is [snap_lo, snap_hi) (empty when equal).  Both ranges
-  // are contiguous and disjoint.
-  long long lat_start, lat_count, lat_limit;
-  long long snap_lo, snap_hi;
-  long long snap_hist_used;  // snapshot of hist_used
-  int32_t snap_status, snap_frames;   // snapshot of status and num_frames
+  // Lattice records of a channel live in a ring of lat_cap records: record number v (counted
+  // from init) sits at v % lat_cap.  Records [lat_head, lat_total) have not been handed out.
+  // lat_head belongs to the readouts (they may run while the channel is being decoded), every
+  // other field to the lane kernel.
+  long long lat_head;
   long long lat_total;       // lattice records produced since init
   long long arcs_expanded;
   int32_t max_pre, max_post, closure_iters_max;
   int32_t path_nf;           // frames covered by the remembered best path (0 = none)
 };
 
+// The state of a channel sealed at a frame boundary, for readouts that run while later
+// frames are being decoded.  A channel keeps its last SNAP_RING snapshots; id 0 is none.
+constexpr int SNAP_RING = 256;
+struct __align__(16) ChanSnap {
+  long long id;              // written last
+  long long lat_total;       // lattice records produced up to the boundary
+  long long hist_used;
+  int32_t status, num_frames;
+};
+
 struct LaneParam {
   const float *ll;           // device rows of this lane
-  int32_t chan, n_frames, stride, pad;
+  int32_t chan, n_frames, stride;
+  int32_t snap_every;        // seal a snapshot after every snap_every frames of the call (0: none)
+  long long snap_id0;        // id of the call's first snapshot
+  int32_t n_snaps, pad;      // snapshots the lane seals in this call (the last ones at its end state)
 };
 
 struct DecDev {
   GraphDev g;
   ChanState *chan;
+  ChanSnap *snap;            // [num_channels][SNAP_RING]
+  long long *lane_sealed;    // [max_lanes] pinned host memory: id of the last snapshot a lane sealed
   long long *frame_off;      // [num_channels][max_frames + 2] start of each frame in hist
   HTok *hist;                // [num_channels][hist_cap]
   LatInt *lat;               // [num_channels][lat_cap]

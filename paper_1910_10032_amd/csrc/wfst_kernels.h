@@ -121,7 +121,8 @@ struct LaneShared {
   unsigned long long emit_arcs, eps_arcs;
   // channel state, cached for the duration of the call
   int status, nf, max_pre, max_post, iters_max, n_in;
-  long long in_off, hist_used, lat_count, lat_room, lat_total, arcs_expanded;
+  long long in_off, hist_used, lat_room, lat_total, arcs_expanded;
+  long long lat_pos;           // ring position of record number lat_total
 #ifdef WFST_PHASE_TIMING
   unsigned long long ph[16], tlast, dbg_tok, dbg_iters, dbg_arcs;
 #endif
@@ -535,12 +536,16 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
 
   // ---- 5. lattice records and back-pointers ---------------------------------------------
   if (abort_code == 0) {
-    const long long lat_base = S.lat_count;
+    const long long lat_base = S.lat_pos;
     const uint32_t n_aux = min(S.auxn, (uint32_t)D.auxcap);
     auto emit_lat = [&](uint32_t arc, float extra, uint32_t dst, uint32_t src) {
       const uint32_t p = wave_alloc(&S.latn);
-      if (lat_base + (long long)p >= S.lat_room) atomicOr(&S.flags, F_LATOVF);
-      else lat[lat_base + p] = LatInt{nf, arc, extra, dst, src};
+      if ((long long)p >= S.lat_room) atomicOr(&S.flags, F_LATOVF);
+      else {
+        long long at = lat_base + (long long)p;
+        if (at >= D.lat_cap) at -= D.lat_cap;
+        lat[at] = LatInt{nf, arc, extra, dst, src};
+      }
     };
     for (uint32_t i0 = 0; i0 < n_aux; i0 += NT * LAT_U) {
       Aux a[LAT_U];
@@ -600,14 +605,16 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
   }
   if (tid == 0) {
     if (abort_code == 0 && (S.flags & F_LATOVF)) abort_code = E_LATTICE_OVERFLOW;
-    const long long lat_new = min((long long)S.latn, max(0ll, S.lat_room - S.lat_count));
+    const long long lat_new = min((long long)S.latn, S.lat_room);
     if (nf <= D.max_frames) {
       foff[nf + 1] = out_base + n_out;
       S.nf = nf + 1;
       S.in_off = out_base; S.n_in = (int)n_out;      // the frame just written is what the next one expands
     }
     S.hist_used = out_base + n_out;
-    S.lat_count += lat_new; S.lat_total += lat_new;
+    S.lat_total += lat_new; S.lat_room -= lat_new;
+    S.lat_pos += lat_new;
+    if (S.lat_pos >= D.lat_cap) S.lat_pos -= D.lat_cap;
     S.arcs_expanded += (long long)(S.emit_arcs + S.eps_arcs);
     S.max_pre = max(S.max_pre, (int)S.nvalid);
     S.max_post = max(S.max_post, (int)n_out);
@@ -636,18 +643,19 @@ __global__ void __launch_bounds__(NT, NT / 128) k_advance(DecDev D, const LanePa
   uint32_t *dslot = D.dslot + (size_t)blockIdx.x * (size_t)D.tokcap;
   long long *foff = D.frame_off + (size_t)lp.chan * (size_t)(D.max_frames + 2);
   HTok *hist = D.hist + (size_t)lp.chan * (size_t)D.hist_cap;
-  LatInt *lat = D.lat + (size_t)lp.chan * (size_t)D.lat_cap + (is_init ? 0 : (size_t)cs->lat_start);
+  LatInt *lat = D.lat + (size_t)lp.chan * (size_t)D.lat_cap;
 
   const Slot fresh{~0ull, EMPTY, A_FRESH};
   for (int i = tid; i < LDS_SLOTS; i += NT) S.table[i] = fresh;
   if (tid == 0) {
     if (is_init) {
-      S.status = 0; S.nf = 0; S.hist_used = 0; S.lat_count = 0; S.lat_room = D.lat_cap; S.lat_total = 0; S.arcs_expanded = 0;
+      S.status = 0; S.nf = 0; S.hist_used = 0; S.lat_room = D.lat_cap; S.lat_pos = 0; S.lat_total = 0; S.arcs_expanded = 0;
       S.max_pre = 0; S.max_post = 0; S.iters_max = 0;
       foff[0] = 0;
     } else {
-      S.status = cs->status; S.nf = cs->num_frames; S.hist_used = cs->hist_used; S.lat_count = cs->lat_count;
-      S.lat_room = cs->lat_limit - cs->lat_start;
+      S.status = cs->status; S.nf = cs->num_frames; S.hist_used = cs->hist_used;
+      S.lat_room = D.lat_cap - (cs->lat_total - (long long)ld64((const unsigned long long *)&cs->lat_head));
+      S.lat_pos = cs->lat_total % D.lat_cap;
       S.lat_total = cs->lat_total; S.arcs_expanded = cs->arcs_expanded; S.max_pre = cs->max_pre;
       S.max_post = cs->max_post; S.iters_max = cs->closure_iters_max;
     }
@@ -660,7 +668,26 @@ __global__ void __launch_bounds__(NT, NT / 128) k_advance(DecDev D, const LanePa
 #endif
   }
   __syncthreads();
+  // Seal the lane's state as snapshot number `j` of this call: everything the workgroup has
+  // written so far is made visible to the whole system, then the snapshot entry and the
+  // lane's progress word.  Readouts of the snapshot start only after the host has seen the
+  // progress words of all lanes, so they never wait inside a kernel.
+  int n_sealed = 0;
+  auto seal = [&]() {
+    __syncthreads();                                  // all waves' stores have been issued and acknowledged
+    if (tid == 0) {
+      const long long id = lp.snap_id0 + n_sealed;
+      ChanSnap *sp = D.snap + (size_t)lp.chan * SNAP_RING + (size_t)(id % SNAP_RING);
+      sp->lat_total = S.lat_total; sp->hist_used = S.hist_used; sp->status = S.status; sp->num_frames = S.nf;
+      sp->id = id;
+      // space freed by drains that ran beside this call
+      S.lat_room = D.lat_cap - (S.lat_total - (long long)ld64((const unsigned long long *)&cs->lat_head));
+      __hip_atomic_store(D.lane_sealed + blockIdx.x, id, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    ++n_sealed;
+  };
   const int nframes = is_init ? 1 : lp.n_frames;
+  int until_seal = (!is_init && lp.snap_every > 0) ? lp.snap_every : 0x7FFFFFFF;
   for (int f = 0; f < nframes; ++f) {
     if (S.status != 0) break;
     const float *ll = is_init ? nullptr : lp.ll + (size_t)f * (size_t)lp.stride;
@@ -678,16 +705,18 @@ __global__ void __launch_bounds__(NT, NT / 128) k_advance(DecDev D, const LanePa
 #ifdef WFST_PHASE_TIMING
     if (tid == 0) S.ph[5] += 1;
 #endif
+    if (--until_seal == 0) {
+      if (n_sealed < lp.n_snaps) seal();
+      until_seal = lp.snap_every;
+    }
   }
+  if (!is_init) while (n_sealed < lp.n_snaps) seal();  // a lane that ran out of frames, or stopped, seals the rest as it is
   __syncthreads();
   if (tid == 0) {
-    cs->status = S.status; cs->num_frames = S.nf; cs->hist_used = S.hist_used; cs->lat_count = S.lat_count;
+    cs->status = S.status; cs->num_frames = S.nf; cs->hist_used = S.hist_used;
     cs->lat_total = S.lat_total; cs->arcs_expanded = S.arcs_expanded; cs->max_pre = S.max_pre;
     cs->max_post = S.max_post; cs->closure_iters_max = S.iters_max;
-    if (is_init) {
-      cs->path_nf = 0; cs->lat_start = 0; cs->lat_limit = D.lat_cap; cs->snap_lo = 0; cs->snap_hi = 0;
-      cs->snap_status = 0; cs->snap_frames = 0; cs->snap_hist_used = 0;
-    }
+    if (is_init) { cs->path_nf = 0; cs->lat_head = 0; }
 #ifdef WFST_PHASE_TIMING
     if (D.dbg) {
       for (int k = 0; k < 8; ++k) atomicAdd(D.dbg + k, S.ph[k]);
@@ -716,17 +745,26 @@ struct PathOut { int32_t status, n_words, n_arcs, reached_final; float total_cos
 // Arg-min over the last frame of a channel by the whole wave: packed (ordered cost, handle)
 // minimum over all tokens and, if asked for, over tokens in final states (cost + final cost).
 // Returns false if the channel has an error or no token; lane 0 gets the start of the walk.
-// snap: read the channel as it was when the last snapshot was taken (status, frame count).
-__device__ __forceinline__ bool path_start(const DecDev &D, int ch, int use_final, int snap, PathOut &po, int &F, int &cur) {
+// The channel's state as the readouts see it: live, or as sealed in snapshot `snap_id` (> 0).
+struct ChanView { int status, num_frames; long long hist_used, lat_total; };
+__device__ __forceinline__ ChanView chan_view(const DecDev &D, int ch, long long snap_id) {
+  if (snap_id <= 0) {
+    const ChanState *cs = D.chan + ch;
+    return ChanView{cs->status, cs->num_frames, cs->hist_used, cs->lat_total};
+  }
+  const ChanSnap *sp = D.snap + (size_t)ch * SNAP_RING + (size_t)(snap_id % SNAP_RING);
+  if (sp->id != snap_id) return ChanView{E_NOT_INIT, 0, 0, 0};     // the channel has no such snapshot (any more)
+  return ChanView{sp->status, sp->num_frames, sp->hist_used, sp->lat_total};
+}
+
+__device__ __forceinline__ bool path_start(const DecDev &D, int ch, int use_final, const ChanView &cv, PathOut &po, int &F, int &cur) {
   const int lane = threadIdx.x;
-  const ChanState *cs = D.chan + ch;
   const long long *foff = D.frame_off + (size_t)ch * (size_t)(D.max_frames + 2);
   const HTok *hist = D.hist + (size_t)ch * (size_t)D.hist_cap;
   const uint32_t *rec = D.g.rec;
-  const int st = snap ? cs->snap_status : cs->status;
-  if (st != 0) { po.status = st; return false; }
-  F = (snap ? cs->snap_frames : cs->num_frames) - 1;
-  if (F < 0) { po.status = E_NOT_INIT; return false; }      // no snapshot has been taken
+  if (cv.status != 0) { po.status = cv.status; return false; }
+  F = cv.num_frames - 1;
+  if (F < 0) { po.status = E_NOT_INIT; return false; }
   const long long o = foff[F];
   const int n = (int)(foff[F + 1] - o);
   unsigned long long bf = ~0ull, bn = ~0ull; int bfi = -1, bni = -1;
@@ -758,22 +796,22 @@ __device__ __forceinline__ bool path_start(const DecDev &D, int ch, int use_fina
 // Best path of one channel with its arcs (one wave; lane 0 follows the back-pointers over the
 // whole utterance).  Words / arcs are written right-aligned into cap-sized regions, so a
 // single backward walk leaves them in path order.
-__global__ void __launch_bounds__(64) k_best_path(DecDev D, const int32_t *chans, int use_final, int snap,
+__global__ void __launch_bounds__(64) k_best_path(DecDev D, const int32_t *chans, int use_final, long long snap_id,
                                                   int32_t *words, int words_cap, uint32_t *arcs, int arcs_cap,
                                                   PathOut *out) {
   const int ch = chans[blockIdx.x];
-  const ChanState *cs = D.chan + ch;
   const long long *foff = D.frame_off + (size_t)ch * (size_t)(D.max_frames + 2);
   const HTok *hist = D.hist + (size_t)ch * (size_t)D.hist_cap;
   PathOut po{0, 0, 0, 0, 0.f, 0, 0};
   int F = 0, cur = 0;
-  const bool ok = path_start(D, ch, use_final, snap, po, F, cur);
+  const ChanView cv = chan_view(D, ch, snap_id);
+  const bool ok = path_start(D, ch, use_final, cv, po, F, cur);
   if (threadIdx.x != 0) return;
   if (!ok) { out[blockIdx.x] = po; return; }
   int32_t *wout = words ? words + (size_t)blockIdx.x * words_cap : nullptr;
   uint32_t *aout = arcs ? arcs + (size_t)blockIdx.x * arcs_cap : nullptr;
   int f = F, nw = 0, na = 0;
-  const long long max_steps = (snap ? cs->snap_hist_used : cs->hist_used) + 1;
+  const long long max_steps = cv.hist_used + 1;
   for (long long step = 0;; ++step) {
     if (cur < 0 || (long long)cur >= foff[f + 1] - foff[f]) { po.status = E_BROKEN_TRACE; break; }
     const HTok t = hist[foff[f] + cur];
@@ -797,7 +835,7 @@ __global__ void __launch_bounds__(64) k_best_path(DecDev D, const int32_t *chans
 // a new trace walks back only until it meets the remembered path (a chunk of frames plus the
 // distance to the merge point, not the whole utterance) and splices the remembered prefix.
 // Words of all channels are packed into `words` at po.word_off (allotted with one atomic add).
-__global__ void __launch_bounds__(64) k_best_path_words(DecDev D, const int32_t *chans, int use_final, int snap, int32_t *words,
+__global__ void __launch_bounds__(64) k_best_path_words(DecDev D, const int32_t *chans, int use_final, long long snap_id, int32_t *words,
                                                         int words_cap, unsigned long long *words_used, PathOut *out) {
   const int ch = chans[blockIdx.x];
   const int lane = threadIdx.x;
@@ -810,12 +848,13 @@ __global__ void __launch_bounds__(64) k_best_path_words(DecDev D, const int32_t 
   __shared__ int sh[4];                      // status, total words, merge frame, F
   PathOut po{0, 0, 0, 0, 0.f, 0, 0};
   int F = 0, cur = 0;
-  const bool ok = path_start(D, ch, use_final, snap, po, F, cur);
+  const ChanView cv = chan_view(D, ch, snap_id);
+  const bool ok = path_start(D, ch, use_final, cv, po, F, cur);
   if (!ok) { if (lane == 0) out[blockIdx.x] = po; return; }
   if (lane == 0) {
     const int cached_nf = cs->path_nf;
     int f = F, k = 0, base = 0, merge_f = 0, status = 0;
-    const long long max_steps = (snap ? cs->snap_hist_used : cs->hist_used) + 1;
+    const long long max_steps = cv.hist_used + 1;
     // the token of the next step is fetched while this step's word label is still on its way
     auto in_frame = [&](int ff, int c) { return ff >= 0 && c >= 0 && (long long)c < foff[ff + 1] - foff[ff]; };
     HTok t{};
@@ -881,64 +920,39 @@ __global__ void k_export_tokens(DecDev D, int ch, long long off, int n, TokOut *
 
 // Lattice records with frame >= from_frame, arc ids translated to the caller's; cnt is
 // the running output count (zeroed by the host).
+// (the n records start at ring position `start`)
 __global__ void k_export_lattice(DecDev D, int ch, long long start, long long n, int from_frame, LatRec *out, long long cap,
                                  unsigned long long *cnt) {
-  const LatInt *lat = D.lat + (size_t)ch * (size_t)D.lat_cap + (size_t)start;
+  const LatInt *lat = D.lat + (size_t)ch * (size_t)D.lat_cap;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) {
-    const LatInt r = lat[i];
+    const LatInt r = lat[start + i < D.lat_cap ? start + i : start + i - D.lat_cap];
     if (r.frame < from_frame) continue;
     const unsigned long long p = atomicAdd(cnt, 1ull);
     if ((long long)p < cap) out[p] = LatRec{r.frame, D.g.orig[r.arc], r.extra};
   }
 }
-// Empty a channel's lattice buffer: with snap only the sealed snapshot, else everything.
-__device__ __forceinline__ void lattice_reset(const DecDev &D, int ch, int snap) {
-  ChanState *cs = D.chan + ch;
-  if (snap) { cs->snap_lo = cs->snap_hi; return; }
-  cs->snap_lo = 0; cs->snap_hi = 0; cs->lat_start = 0; cs->lat_count = 0; cs->lat_limit = D.lat_cap;
-}
-// Records a readout of the channel hands out: the undrained snapshot and, unless snap, the current epoch.
-__device__ __forceinline__ long long lattice_pending(const ChanState *cs, int snap) {
-  const int st = snap ? cs->snap_status : cs->status;
-  const bool readable = st == 0 || st == E_DEAD_CHANNEL || st == E_NAN_INPUT;
+// Records a readout hands out: those not handed out yet, up to the live end or the
+// snapshot's.  A channel stopped by an overflow hands out nothing.
+__device__ __forceinline__ long long lattice_pending(const DecDev &D, int ch, long long snap_id) {
+  const ChanView cv = chan_view(D, ch, snap_id);
+  const bool readable = cv.status == 0 || cv.status == E_DEAD_CHANNEL || cv.status == E_NAN_INPUT;
   if (!readable) return 0;
-  return (cs->snap_hi - cs->snap_lo) + (snap ? 0 : cs->lat_count);
+  return max(0ll, cv.lat_total - D.chan[ch].lat_head);
 }
-__global__ void k_reset_lattice(DecDev D, int ch) { lattice_reset(D, ch, 0); }
-
-// Seal every channel's state for readouts that run while later frames are being decoded:
-// status, frame count and history size are copied, and the lattice records of the current
-// epoch become the snapshot (unless an earlier snapshot has not been drained yet: then the
-// records stay in the current epoch and go into a later snapshot).  The new epoch starts in
-// the larger free part of the channel's region, so both ranges stay contiguous.
-__global__ void k_snapshot(DecDev D, int n_channels) {
-  const int ch = blockIdx.x * blockDim.x + threadIdx.x;
-  if (ch >= n_channels) return;
-  ChanState *cs = D.chan + ch;
-  cs->snap_status = cs->status; cs->snap_frames = cs->num_frames; cs->snap_hist_used = cs->hist_used;
-  if (cs->snap_hi != cs->snap_lo) return;
-  if (cs->lat_count == 0) {
-    cs->snap_lo = 0; cs->snap_hi = 0; cs->lat_start = 0; cs->lat_limit = D.lat_cap;
-    return;
-  }
-  const long long lo = cs->lat_start, hi = cs->lat_start + cs->lat_count;
-  cs->snap_lo = lo; cs->snap_hi = hi; cs->lat_count = 0;
-  if (D.lat_cap - hi >= lo) { cs->lat_start = hi; cs->lat_limit = D.lat_cap; }
-  else { cs->lat_start = 0; cs->lat_limit = lo; }
-}
+__global__ void k_reset_lattice(DecDev D, int ch) { D.chan[ch].lat_head = D.chan[ch].lat_total; }
 
 // Batched drain: counts of the listed channels, then one copy kernel (grid.x = channel,
 // grid.y = slices of that channel's buffer), then the reset.
 // offs[0..n]: exclusive prefix sums of the buffered record counts of the listed channels
 // (channels stopped by an overflow count as empty).  One block.
-__global__ void __launch_bounds__(1024) k_lattice_offsets(DecDev D, const int32_t *chans, int n, int snap, long long *offs) {
+__global__ void __launch_bounds__(1024) k_lattice_offsets(DecDev D, const int32_t *chans, int n, long long snap_id, long long *offs) {
   __shared__ long long part[1024];
   const int tid = threadIdx.x;
   const int per = (n + 1023) / 1024;
   const int b = tid * per, e = min(n, b + per);
   long long sum = 0;
   for (int i = b; i < e; ++i) {
-    sum += lattice_pending(D.chan + chans[i], snap);
+    sum += lattice_pending(D, chans[i], snap_id);
   }
   part[tid] = sum;
   __syncthreads();
@@ -951,27 +965,26 @@ __global__ void __launch_bounds__(1024) k_lattice_offsets(DecDev D, const int32_
   long long run = part[tid] - sum;
   for (int i = b; i < e; ++i) {
     offs[i] = run;
-    run += lattice_pending(D.chan + chans[i], snap);
+    run += lattice_pending(D, chans[i], snap_id);
   }
   if (tid == 1023) offs[n] = part[1023];
 }
 __global__ void k_export_lattice_batch(DecDev D, const int32_t *chans, int n_ch, const long long *offs, LatRec *out, long long cap) {
   if (offs[n_ch] > cap) return;                       // caller's buffer too small: nothing is copied or drained
   const int ch = chans[blockIdx.x];
-  const ChanState *cs = D.chan + ch;
   const LatInt *lat = D.lat + (size_t)ch * (size_t)D.lat_cap;
   const long long o = offs[blockIdx.x], n = offs[blockIdx.x + 1] - o;
-  // the snapshot's records first, then the current epoch's (a count of zero means the channel is unreadable)
-  const long long s_lo = cs->snap_lo, n_snap = cs->snap_hi - s_lo, e_lo = cs->lat_start;
+  if (n <= 0) return;
+  const long long start = D.chan[ch].lat_head % D.lat_cap;
   for (long long i = (long long)blockIdx.y * blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.y * blockDim.x) {
-    const LatInt r = lat[i < n_snap ? s_lo + i : e_lo + (i - n_snap)];
+    const LatInt r = lat[start + i < D.lat_cap ? start + i : start + i - D.lat_cap];
     out[o + i] = LatRec{r.frame, D.g.orig[r.arc], r.extra};
   }
 }
-__global__ void k_reset_lattice_batch(DecDev D, const int32_t *chans, int n, int snap, const long long *offs, long long cap) {
+__global__ void k_reset_lattice_batch(DecDev D, const int32_t *chans, int n, const long long *offs, long long cap) {
   if (offs[n] > cap) return;
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n && offs[i + 1] > offs[i]) lattice_reset(D, chans[i], snap);
+  if (i < n) D.chan[chans[i]].lat_head += offs[i + 1] - offs[i];
 }
 
 // ---- final lattice -------------------------------------------------------------------------
@@ -989,14 +1002,17 @@ __global__ void __launch_bounds__(1024) k_final_lattice(DecDev D, int ch, int us
   const ChanState *cs = D.chan + ch;
   const long long *foff = D.frame_off + (size_t)ch * (size_t)(D.max_frames + 2);
   const HTok *hist = D.hist + (size_t)ch * (size_t)D.hist_cap;
-  const LatInt *lat = D.lat + (size_t)ch * (size_t)D.lat_cap + (size_t)cs->lat_start;
+  const LatInt *lat_ring = D.lat + (size_t)ch * (size_t)D.lat_cap;
+  const long long lat_first = cs->lat_head % D.lat_cap, lat_cap = D.lat_cap;
+  // record i of the buffered ones (they start at ring position lat_first)
+  auto lat = [&](long long i) -> const LatInt & { return lat_ring[lat_first + i < lat_cap ? lat_first + i : lat_first + i - lat_cap]; };
   const uint32_t *rec = D.g.rec;
   __shared__ uint32_t s_best_f, s_best_n, s_changed;
   __shared__ unsigned long long s_kept;
   const int st = cs->status;
   const bool readable = st == 0;
   const int T = cs->num_frames - 1;
-  const long long n_rec = cs->lat_count;
+  const long long n_rec = cs->lat_total - cs->lat_head;
   const long long n_tok = cs->hist_used;
   const long long oT = T >= 0 ? foff[T] : 0;
   const int nT = T >= 0 ? (int)(foff[T + 1] - oT) : 0;
@@ -1010,8 +1026,8 @@ __global__ void __launch_bounds__(1024) k_final_lattice(DecDev D, int ch, int us
   __syncthreads();
   // start of each frame's run of records (records are appended frame by frame)
   for (long long i = tid; i < n_rec; i += NTH) {
-    const int f = lat[i].frame;
-    if (i == 0 || lat[i - 1].frame != f) rec_start[f] = i;
+    const int f = lat(i).frame;
+    if (i == 0 || lat(i - 1).frame != f) rec_start[f] = i;
   }
   // best cost over the last frame
   for (int i = tid; i < nT; i += NTH) {
@@ -1046,7 +1062,7 @@ __global__ void __launch_bounds__(1024) k_final_lattice(DecDev D, int ch, int us
     if (f < T) {                                    // emitting arcs recorded with frame f + 1 start in frame f
       const long long of1 = foff[f + 1];
       for (long long i = rec_start[f + 1] + tid; i < rec_start[f + 2]; i += NTH) {
-        const LatInt r = lat[i];
+        const LatInt r = lat(i);
         if (r.src & PREV_SAME) continue;
         const float v = __uint_as_float(ld32(&te[of1 + r.dst])) + r.extra;
         atomicMin(&te[of + r.src], __float_as_uint(v));
@@ -1058,7 +1074,7 @@ __global__ void __launch_bounds__(1024) k_final_lattice(DecDev D, int ch, int us
       if (tid == 0) s_changed = 0;
       __syncthreads();
       for (long long i = e0 + tid; i < e1; i += NTH) {
-        const LatInt r = lat[i];
+        const LatInt r = lat(i);
         if (!(r.src & PREV_SAME)) continue;
         const uint32_t v = __float_as_uint(__uint_as_float(ld32(&te[of + r.dst])) + r.extra);
         if (v < atomicMin(&te[of + (r.src & ~PREV_SAME)], v)) s_changed = 1;
@@ -1069,7 +1085,7 @@ __global__ void __launch_bounds__(1024) k_final_lattice(DecDev D, int ch, int us
     }
   }
   for (long long i = tid; i < n_rec; i += NTH) {
-    const LatInt r = lat[i];
+    const LatInt r = lat(i);
     const float v = __uint_as_float(ld32(&te[foff[r.frame] + r.dst])) + r.extra;
     if (v <= D.lattice_beam) {
       const unsigned long long p = atomicAdd(&s_kept, 1ull);

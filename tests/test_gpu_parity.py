@@ -349,20 +349,30 @@ def _assert_records(got, want, label):
     assert np.array_equal(got["extra_cost"][o].view(np.uint32), ex.view(np.uint32)), label
 
 
-def test_snapshot_readouts_beside_decoding(torch_cuda, B):
-    """Readouts of a sealed snapshot while the next chunk is being decoded (the paper's second
-    stream, Section 3): per-chunk best paths and lattice records must be those of the checker
-    at the snapshot's frame, whatever has been queued behind it.  The lattice buffer is
-    small, so the epochs wrap around the channel's region several times; one channel skips
-    drains, which must delay its records, not lose them."""
+def _check_paths(got, ods_at, use_final, label):
+    for ch, (r, od) in enumerate(zip(got, ods_at)):
+        want = od.best_path(use_final)
+        assert r["status"] == 0, f"{label} ch {ch}: status {r['status']}"
+        assert np.array_equal(r["words"], want["words"]), f"{label} ch {ch}"
+        assert np.float32(r["total_cost"]).view(np.uint32) == np.float32(want["total_cost"]).view(np.uint32), f"{label} ch {ch}"
+        assert r["reached_final"] == want["reached_final"], f"{label} ch {ch}"
+
+
+def test_snapshots_sealed_inside_one_call(torch_cuda, B):
+    """One advance call over the whole (ragged) utterances with a snapshot every 10 frames: the
+    lanes seal their state at each boundary and go on; best paths and lattice records of every
+    snapshot, read while the call may still be running, must be the checker's at that frame.
+    One channel skips drains, which must delay its records, not lose them; a lane shorter
+    than the call seals the remaining snapshots at its end state."""
     torch = torch_cuda
     c = synth.configs()[0]
     g = synth.make_graph(c.graph)
-    n, T, chunk = 4, 160, 10
-    rows = [c.loglikes(s, 0, T) for s in range(n)]
+    lens, chunk = [160, 160, 95, 160], 10
+    n, T = len(lens), max(lens)
+    rows = [c.loglikes(s, 0, lens[s]) for s in range(n)]
     gg = B.WfstGraph(g)
     dec = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=n, max_lanes=n, max_frames=T,
-                        lattice_capacity=70_000)
+                        lattice_capacity=300_000)
     chans = list(range(n))
     dec.init_channels(chans)
     dev = [torch.from_numpy(r).cuda() for r in rows]
@@ -370,44 +380,72 @@ def test_snapshot_readouts_beside_decoding(torch_cuda, B):
     ods = [oracle.OracleDecoder(og, c.beam, c.lattice_beam, c.max_active) for _ in range(n)]
     for od, r in zip(ods, rows):
         od.advance(r)
-    full = [oracle.OracleDecoder(og, c.beam, c.lattice_beam, c.max_active) for _ in range(n)]
-    side = torch.cuda.Stream()
-    nchunks = T // chunk
-    drained_to = [0] * n                       # first frame not yet handed out, per channel
-    sealed_to = [0] * n                        # end of the frames in the channel's undrained snapshot
-    with torch.cuda.stream(side):
-        dec.advance(chans, [d[0:chunk] for d in dev])
-        for k in range(nchunks):
-            end = (k + 1) * chunk + 1          # frames [0, end) exist in the snapshot
-            dec.snapshot()
-            for ch in chans:
-                if sealed_to[ch] == drained_to[ch]:
-                    sealed_to[ch] = end        # the previous snapshot was drained: a new one is taken
-            if k + 1 < nchunks:
-                dec.advance(chans, [d[(k + 1) * chunk:(k + 2) * chunk] for d in dev])
-            for od, r in zip(full, rows):
-                od.advance(r[k * chunk:(k + 1) * chunk])
-            got = dec.best_path_batch(chans, use_final=(k % 2 == 0), snapshot=True)
-            for ch, (r, od) in enumerate(zip(got, full)):
-                want = od.best_path(k % 2 == 0)
-                assert r["status"] == 0
-                assert np.array_equal(r["words"], want["words"]), f"chunk {k} ch {ch}"
-                assert np.float32(r["total_cost"]).view(np.uint32) == np.float32(want["total_cost"]).view(np.uint32)
-            listed = [ch for ch in chans if not (ch == 3 and k % 3 != 2)]   # channel 3 is drained every third chunk
-            recs, offs = dec.lattice_arcs_batch(listed, snapshot=True)
-            for i, ch in enumerate(listed):
-                _assert_records(recs[offs[i]:offs[i + 1]], _oracle_lattice_of_frames(ods[ch], drained_to[ch], sealed_to[ch]),
-                                f"chunk {k} ch {ch}")
-                drained_to[ch] = sealed_to[ch]
+    step = [oracle.OracleDecoder(og, c.beam, c.lattice_beam, c.max_active) for _ in range(n)]
+    drained_to = [0] * n
+    with torch.cuda.stream(torch.cuda.Stream()):
+        first, count = dec.advance(chans, dev, snapshot_every=chunk)
+    assert count == T // chunk and first >= 1
+    for j in range(count):
+        for od, r in zip(step, rows):
+            if len(r[j * chunk:(j + 1) * chunk]):             # nothing once the stream has ended
+                od.advance(r[j * chunk:(j + 1) * chunk])
+        _check_paths(dec.best_path_batch(chans, use_final=(j % 2 == 0), snapshot=first + j), step, j % 2 == 0, f"snapshot {j}")
+        listed = [ch for ch in chans if not (ch == 3 and j % 3 != 2)]   # channel 3 is drained every third snapshot
+        recs, offs = dec.lattice_arcs_batch(listed, snapshot=first + j)
+        for i, ch in enumerate(listed):
+            end = min((j + 1) * chunk, lens[ch]) + 1
+            _assert_records(recs[offs[i]:offs[i + 1]], _oracle_lattice_of_frames(ods[ch], drained_to[ch], end), f"snapshot {j} ch {ch}")
+            drained_to[ch] = end
     torch.cuda.synchronize()
-    for ch in chans:
-        assert dec.stats(ch)["status"] == 0
-    # what is left (channel 3: the chunks after its last snapshot) comes out of the live drain
+    # what is left (channel 3: the frames after its last drain) comes out of the live drain
     recs, offs = dec.lattice_arcs_batch(chans)
     for ch in chans:
         _assert_records(recs[offs[ch]:offs[ch + 1]], _oracle_lattice_of_frames(ods[ch], drained_to[ch], T + 1), f"rest ch {ch}")
     for ch in chans:
         compare_channel(dec, ch, ods[ch], label=f"snapshot-flow ch{ch}", lattice=False)
+
+
+def test_snapshot_pipeline_over_calls_wraps_the_lattice_ring(torch_cuda, B):
+    """Chunk k + 1 is queued before chunk k's snapshot is read, call after call; the lattice
+    ring is a few chunks long, so it wraps many times and space must come back from the
+    drains that run beside the decoding."""
+    torch = torch_cuda
+    c = synth.configs()[0]
+    g = synth.make_graph(c.graph)
+    n, T, chunk = 3, 200, 10
+    rows = [c.loglikes(s, 0, T) for s in range(n)]
+    og = oracle.OracleGraph(g)
+    ods = [oracle.OracleDecoder(og, c.beam, c.lattice_beam, c.max_active) for _ in range(n)]
+    for od, r in zip(ods, rows):
+        od.advance(r)
+    per_chunk = max(len(_oracle_lattice_of_frames(od, f0 + 1, f0 + chunk + 1)[0]) for od in ods for f0 in range(0, T, chunk))
+    gg = B.WfstGraph(g)
+    dec = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=n, max_lanes=n, max_frames=T,
+                        lattice_capacity=int(3.5 * per_chunk))
+    chans = list(range(n))
+    dec.init_channels(chans)
+    dev = [torch.from_numpy(r).cuda() for r in rows]
+    step = [oracle.OracleDecoder(og, c.beam, c.lattice_beam, c.max_active) for _ in range(n)]
+    nchunks = T // chunk
+    with torch.cuda.stream(torch.cuda.Stream()):
+        ids = [dec.advance(chans, [d[0:chunk] for d in dev], snapshot_every=chunk)[0]]
+        for k in range(nchunks):
+            if k + 1 < nchunks:
+                first, count = dec.advance(chans, [d[(k + 1) * chunk:(k + 2) * chunk] for d in dev], snapshot_every=chunk)
+                assert count == 1
+                ids.append(first)
+            for od, r in zip(step, rows):
+                od.advance(r[k * chunk:(k + 1) * chunk])
+            _check_paths(dec.best_path_batch(chans, use_final=False, snapshot=ids[k]), step, False, f"chunk {k}")
+            recs, offs = dec.lattice_arcs_batch(chans, snapshot=ids[k])
+            for ch in chans:
+                lo = 0 if k == 0 else k * chunk + 1
+                _assert_records(recs[offs[ch]:offs[ch + 1]], _oracle_lattice_of_frames(ods[ch], lo, (k + 1) * chunk + 1), f"chunk {k} ch {ch}")
+    torch.cuda.synchronize()
+    assert ids == sorted(set(ids))
+    for ch in chans:
+        assert dec.stats(ch)["status"] == 0 and dec.stats(ch)["lattice_arcs"] == len(ods[ch].lattice()[0])
+        compare_channel(dec, ch, ods[ch], label=f"ring ch{ch}", lattice=False)
 
 
 def test_snapshot_edge_cases(torch_cuda, B):
@@ -423,28 +461,39 @@ def test_snapshot_edge_cases(torch_cuda, B):
     dec = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=2, max_lanes=2, max_frames=40,
                         lattice_capacity=200_000)
     dec.init_channels([0, 1])
-    # no snapshot yet
-    with pytest.raises(B.WfstError) as e:
-        dec.best_path_batch([0], snapshot=True)
-    assert e.value.code == B.WFST_E_NOT_INIT
-    dec.advance([0], [t[:20]])
-    dec.snapshot()
+    for bad in (1, 12345):                      # ids no call has produced
+        with pytest.raises(B.WfstError) as e:
+            dec.best_path_batch([0], snapshot=bad)
+        assert e.value.code == B.WFST_E_NOT_INIT
+    first, count = dec.advance([0], [t[:20]], snapshot_every=20)
+    assert count == 1
     dec.advance([0], [t[20:40]])
-    # a live drain with an undrained snapshot hands out both, and the final lattice sees the
-    # current epoch only
-    recs = dec.lattice_arcs(0)
-    _assert_records(recs, _oracle_lattice_of_frames(od, 0, 41), "live drain after snapshot")
-    # channel 1 was initialised but never advanced: its snapshot is frame 0
-    r = dec.best_path_batch([1], use_final=False, snapshot=True)[0]
-    assert r["status"] == 0 and len(r["words"]) == 0
-    # an epoch that outgrows the room left beside an undrained snapshot stops the channel cleanly
+    # channel 1 was not in the call: it has no such snapshot
+    r = dec.best_path_batch([0, 1], use_final=False, snapshot=first)
+    assert r[0]["status"] == 0 and r[1]["status"] == B.WFST_E_NOT_INIT
+    assert np.array_equal(r[0]["words"], (lambda o: (o.advance(rows[:20]), o.best_path(False)["words"])[1])(
+        oracle.OracleDecoder(og, c.beam, c.lattice_beam, c.max_active)))
+    recs, offs = dec.lattice_arcs_batch([1, 0], snapshot=first)
+    assert offs[1] == 0
+    _assert_records(recs, _oracle_lattice_of_frames(od, 0, 21), "snapshot drain")
+    # the live drain hands out the rest; a snapshot older than the drain point has nothing left
+    _assert_records(dec.lattice_arcs(0), _oracle_lattice_of_frames(od, 21, 41), "live drain after a snapshot drain")
+    recs, offs = dec.lattice_arcs_batch([0], snapshot=first)
+    assert offs[-1] == 0
+    # a call with zero frames still seals its snapshot (the state as it is)
+    first2, count2 = dec.advance([0], [t[:0]], snapshot_every=5)
+    assert count2 == 1 and first2 == first + 1
+    r = dec.best_path_batch([0], use_final=True, snapshot=first2)[0]
+    assert np.array_equal(r["words"], od.best_path(True)["words"])
+    # a ring too small for the arcs of one call stops the channel cleanly; the snapshot sealed before is intact
+    need = len(_oracle_lattice_of_frames(od, 0, 21)[0])
     small = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=1, max_lanes=1, max_frames=40,
-                          lattice_capacity=int(len(_oracle_lattice_of_frames(od, 0, 21)[0]) * 1.3))
+                          lattice_capacity=int(need * 1.3))
     small.init_channels([0])
-    small.advance([0], [t[:20]])
-    small.snapshot()
-    small.advance([0], [t[20:40]])
+    first, count = small.advance([0], [t], snapshot_every=20)
+    assert count == 2
     torch.cuda.synchronize()
     assert small.stats(0)["status"] == B.WFST_E_LATTICE_OVERFLOW
-    recs, offs = small.lattice_arcs_batch([0], snapshot=True)      # the snapshot itself is intact
-    _assert_records(recs, _oracle_lattice_of_frames(od, 0, 21), "snapshot of an overflowed channel")
+    recs, offs = small.lattice_arcs_batch([0], snapshot=first)
+    _assert_records(recs, _oracle_lattice_of_frames(od, 0, 21), "snapshot of a channel that overflowed later")
+    assert small.best_path_batch([0], snapshot=first + 1)[0]["status"] == B.WFST_E_LATTICE_OVERFLOW
