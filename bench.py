@@ -49,6 +49,9 @@ def main() -> int:
     ap.add_argument("--cpu-streams", type=int, default=12)
     ap.add_argument("--sync-readout", action="store_true",
                     help="one call per chunk, read out before the next one is queued (no overlap with decoding)")
+    ap.add_argument("--copy-lattice", action="store_true",
+                    help="also copy each snapshot's lattice block from the decoder's memory into a buffer of the caller "
+                         "(default: the block is handed over in place, by address and per-channel ranges)")
     ap.add_argument("--chunks-per-call", type=int, default=0,
                     help="chunks one advance call covers (0: all chunks of the warm-up / of the timed region)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -93,7 +96,7 @@ def main() -> int:
     torch.cuda.synchronize()
     dec = B.WfstDecoder(graph, cfg.beam, cfg.lattice_beam, cfg.max_active, num_channels=n_ch, max_lanes=n_ch,
                         max_frames=n_frames, token_capacity=16384, history_capacity=2_500_000,
-                        lattice_capacity=1_000_000)
+                        lattice_capacity=400_000, snapshot_blocks=max(K, W, 1), snapshot_block_capacity=16_000 * n_ch)
     ch_np = np.arange(n_ch, dtype=np.int32)
     dec.init_channels(ch_np)
     stream = torch.cuda.Stream().cuda_stream
@@ -109,9 +112,13 @@ def main() -> int:
                                 snapshot_every)
 
     def read(snapshot: int = 0):
+        """Best path of every channel and its lattice arcs since the last readout, in device
+        memory in the caller's form: returns (paths, number of arcs)."""
         paths = dec.best_path_batch(ch_np, use_final=False, words_cap=1024, raw=True, snapshot=snapshot)
-        offs = dec.lattice_arcs_batch(ch_np, out_device=lat_buf, snapshot=snapshot)
-        return paths, offs
+        if snapshot:
+            r = dec.snapshot_lattice_arcs(snapshot, ch_np, out_device=lat_buf, copy=args.copy_lattice)
+            return paths, int(r["total"])
+        return paths, int(dec.lattice_arcs_batch(ch_np, out_device=lat_buf)[-1])
 
     def all_stats():
         return [dec.stats(int(c)) for c in ch_np]
@@ -195,7 +202,7 @@ def main() -> int:
         "setup_s": round(t0 - t_setup, 1),
     }
     if readout:
-        result["lattice_arcs_last_chunk"] = int(last[1][-1])
+        result["lattice_arcs_last_chunk"] = int(last[1])
 
     if not args.no_cpu_baseline:
         import oracle

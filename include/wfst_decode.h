@@ -93,6 +93,11 @@ typedef struct {
   int64_t lattice_capacity;  /* lattice arcs one channel can buffer between readouts;
                                 0 = 64 * max_active                                         */
   int32_t lattice_on;        /* 0: no lattice arcs are produced                             */
+  int32_t snapshot_blocks;   /* blocks for the lattice arcs of sealed snapshots (see
+                                wfst_decode_advance_snapshots); 0 = none: snapshots then
+                                cover best paths only                                       */
+  int64_t snapshot_block_capacity; /* lattice arcs one block holds, all lanes of a call
+                                together; 0 = min(lattice_capacity, 4096 * max_lanes)     */
 } wfst_config_t;
 
 typedef struct { int32_t frame; uint32_t arc; float extra_cost; } wfst_lat_arc_t;
@@ -195,28 +200,38 @@ int wfst_decode_lattice_arcs_batch(wfst_decoder_t *decoder, const int32_t *chann
  *
  * wfst_decode_advance_snapshots is wfst_decode_advance with one addition: after every
  * snapshot_every (>= 1) frames of the call each lane seals a snapshot of its channel - its
- * status and frame count, and how many lattice arcs it had produced - and goes on decoding.
+ * status and frame count - and goes on decoding.  If the decoder has snapshot blocks, the
+ * lane also moves the channel's lattice arcs not handed out yet into the snapshot's block,
+ * in the caller's form; without blocks the arcs stay buffered for wfst_decode_lattice_arcs*.
  * The call seals *n_snapshots = max(1, ceil(longest n_frames / snapshot_every)) snapshots
- * (at most 256) with consecutive ids starting at *first_id (ids are positive and grow over
- * the decoder's life); a lane with fewer frames, or one that stops with an error, seals the
- * remaining ones in the state it ends in.  Lanes do not wait for each other at the
- * boundaries, so one call over many chunks keeps the whole GPU busy although the chunks
- * differ from lane to lane; a channel keeps its last 256 snapshots.
+ * (at most 256, and at most snapshot_blocks if there are blocks) with consecutive ids
+ * starting at *first_id (ids are positive and grow over the decoder's life); a lane with
+ * fewer frames, or one that stops with an error, seals the remaining ones in the state it
+ * ends in.  Lanes do not wait for each other at the boundaries, so one call over many
+ * chunks keeps the whole GPU busy although the chunks differ from lane to lane.  A channel
+ * keeps its last 256 snapshots; snapshot id uses block id % snapshot_blocks, so a block is
+ * valid until snapshot_blocks later snapshots have been started.  A block that cannot take
+ * a lane's arcs stops that channel with WFST_E_LATTICE_OVERFLOW.
  *
  * wfst_decode_snapshot_wait blocks the calling host thread until every lane of the call has
  * sealed snapshot `id` (WFST_E_NOT_INIT for an id no recent call has produced).  The two
- * readouts below wait likewise and then do what wfst_decode_best_path_batch and
- * wfst_decode_lattice_arcs_batch do, on the snapshot: best paths end at the snapshot's last
- * frame; the lattice readout hands out and drains the arcs not handed out before, up to the
- * snapshot (so snapshots read in order give each chunk's arcs, and a skipped one is not
- * lost).  They run on a stream of the decoder's own and synchronise with that stream alone,
- * so the lanes go on decoding while they run.  A listed channel without that snapshot
- * reports WFST_E_NOT_INIT in status[i] / contributes no arcs.  While an advance call is in
- * flight use only these readouts on its channels; every other readout of this header refers
- * to the live state and waits for the decoding.  A DEVICE output buffer is written on the
- * decoder's own stream and is complete when the call returns.  Lattice arcs that have not
- * been handed out occupy the channel's lattice_capacity; arcs drained beside a running call
- * free their space for that same call. */
+ * readouts below wait likewise, run on a stream of the decoder's own and synchronise with
+ * that stream alone, so the lanes go on decoding while they run.  While an advance call is
+ * in flight use only these readouts on its channels; every other readout of this header
+ * refers to the live state and waits for the decoding.
+ *
+ * wfst_decode_snapshot_best_path_batch: as wfst_decode_best_path_batch, with paths ending
+ * at the snapshot's last frame.  A listed channel without that snapshot reports
+ * WFST_E_NOT_INIT in status[i].
+ *
+ * wfst_decode_snapshot_lattice_arcs: the lattice arcs of the snapshot, i.e. for every lane
+ * of the call the arcs produced since its previous hand-over.  The block holds *total arcs,
+ * all lanes together, in no particular order; channel i's are at [starts[i], starts[i] +
+ * counts[i]) (HOST [n]; 0, 0 for a channel without that snapshot).  If out != NULL the
+ * whole block is copied to it (HOST or DEVICE as flagged; WFST_E_CAPACITY with *total set
+ * if cap < *total); if block != NULL it receives the DEVICE address of the decoder's own
+ * block, for consumers that read the arcs in place.  WFST_E_NOT_INIT if the block has been
+ * given to a later snapshot; WFST_E_INVALID_ARG if the decoder has no snapshot blocks. */
 int wfst_decode_advance_snapshots(wfst_decoder_t *decoder, const int32_t *channels, int32_t n_lanes,
                                   const float *const *loglikes, const int32_t *strides,
                                   const int32_t *n_frames, int32_t snapshot_every, void *stream,
@@ -226,9 +241,11 @@ int wfst_decode_snapshot_best_path_batch(wfst_decoder_t *decoder, int64_t snapsh
                                          const int32_t *channels, int32_t n, int32_t use_final,
                                          int32_t *words, int32_t words_cap, int32_t *n_words,
                                          float *total_cost, int32_t *reached_final, int32_t *status);
-int wfst_decode_snapshot_lattice_arcs_batch(wfst_decoder_t *decoder, int64_t snapshot_id,
-                                            const int32_t *channels, int32_t n, wfst_lat_arc_t *out,
-                                            int64_t cap, int64_t *offsets, int32_t out_is_device);
+int wfst_decode_snapshot_lattice_arcs(wfst_decoder_t *decoder, int64_t snapshot_id,
+                                      const int32_t *channels, int32_t n, int64_t *starts,
+                                      int64_t *counts, wfst_lat_arc_t *out, int64_t cap,
+                                      int32_t out_is_device, int64_t *total,
+                                      const wfst_lat_arc_t **block);
 
 /* Final lattice of a channel (the step the paper leaves to the end of the utterance, Section
  * 3.4): backward pruning, with the lattice beam, of the lattice arcs currently buffered for

@@ -25,7 +25,7 @@ EXPORTS = [
     "wfst_decode_destroy", "wfst_decode_state_bytes", "wfst_decode_init_channels", "wfst_decode_free_channels",
     "wfst_decode_advance", "wfst_decode_best_path_batch", "wfst_decode_best_path", "wfst_decode_best_path_arcs",
     "wfst_decode_lattice_arcs", "wfst_decode_lattice_arcs_batch", "wfst_decode_advance_snapshots",
-    "wfst_decode_snapshot_wait", "wfst_decode_snapshot_best_path_batch", "wfst_decode_snapshot_lattice_arcs_batch", "wfst_decode_final_lattice", "wfst_decode_tokens", "wfst_decode_stats", "wfst_decode_set_profiling",
+    "wfst_decode_snapshot_wait", "wfst_decode_snapshot_best_path_batch", "wfst_decode_snapshot_lattice_arcs", "wfst_decode_final_lattice", "wfst_decode_tokens", "wfst_decode_stats", "wfst_decode_set_profiling",
     "wfst_decode_profile", "wfst_decode_strerror",
 ]
 
@@ -41,7 +41,8 @@ class wfst_config_t(C.Structure):
     _fields_ = [("beam", C.c_float), ("lattice_beam", C.c_float), ("max_active", C.c_int32),
                 ("num_channels", C.c_int32), ("max_lanes", C.c_int32), ("max_frames", C.c_int32),
                 ("token_capacity", C.c_int32), ("aux_capacity", C.c_int32), ("history_capacity", C.c_int64),
-                ("lattice_capacity", C.c_int64), ("lattice_on", C.c_int32)]
+                ("lattice_capacity", C.c_int64), ("lattice_on", C.c_int32), ("snapshot_blocks", C.c_int32),
+                ("snapshot_block_capacity", C.c_int64)]
 
 
 class wfst_stats_t(C.Structure):
@@ -89,7 +90,7 @@ def lib():
         L.wfst_decode_advance_snapshots.argtypes = [vp, vp, i32, vp, vp, vp, i32, vp, C.POINTER(i64), C.POINTER(i32)]
         L.wfst_decode_snapshot_wait.argtypes = [vp, i64]
         L.wfst_decode_snapshot_best_path_batch.argtypes = [vp, i64, vp, i32, i32, vp, i32, vp, vp, vp, vp]
-        L.wfst_decode_snapshot_lattice_arcs_batch.argtypes = [vp, i64, vp, i32, vp, i64, vp, i32]
+        L.wfst_decode_snapshot_lattice_arcs.argtypes = [vp, i64, vp, i32, vp, vp, vp, i64, i32, C.POINTER(i64), C.POINTER(vp)]
         L.wfst_decode_final_lattice.argtypes = [vp, i32, i32, vp, i64, C.POINTER(i64), i32, C.POINTER(wfst_lattice_info_t)]
         L.wfst_decode_tokens.argtypes = [vp, i32, i32, vp, i32, C.POINTER(i32)]
         L.wfst_decode_stats.argtypes = [vp, i32, C.POINTER(wfst_stats_t)]
@@ -147,10 +148,12 @@ class WfstDecoder:
 
     def __init__(self, graph: WfstGraph, beam: float, lattice_beam: float, max_active: int, num_channels: int,
                  max_lanes: int, max_frames: int, token_capacity: int = 0, aux_capacity: int = 0,
-                 history_capacity: int = 0, lattice_capacity: int = 0, lattice_on: bool = True):
+                 history_capacity: int = 0, lattice_capacity: int = 0, lattice_on: bool = True,
+                 snapshot_blocks: int = 0, snapshot_block_capacity: int = 0):
         self.graph = graph
         self.cfg = wfst_config_t(beam, lattice_beam, max_active, num_channels, max_lanes, max_frames, token_capacity,
-                                 aux_capacity, history_capacity, lattice_capacity, int(lattice_on))
+                                 aux_capacity, history_capacity, lattice_capacity, int(lattice_on), snapshot_blocks,
+                                 snapshot_block_capacity)
         self.h = C.c_void_p()
         _check(lib().wfst_decode_create(graph.h, C.byref(self.cfg), C.byref(self.h)), "wfst_decode_create")
 
@@ -291,15 +294,10 @@ class WfstDecoder:
             _check(rc, "wfst_decode_lattice_arcs")
             return out[:n.value].copy()
 
-    def lattice_arcs_batch(self, channels, cap: int = 1 << 20, out_device=None, snapshot: int = 0):
+    def lattice_arcs_batch(self, channels, cap: int = 1 << 20, out_device=None):
         """Drains several channels: (records, offsets) on the host, or offsets only when the
-        records go into the cuda tensor `out_device`.  snapshot = id of a sealed snapshot up to
-        which the arcs are drained, instead of the live state."""
-        if snapshot:
-            def fn(h, *a):
-                return lib().wfst_decode_snapshot_lattice_arcs_batch(h, snapshot, *a)
-        else:
-            fn = lib().wfst_decode_lattice_arcs_batch
+        records go into the cuda tensor `out_device`."""
+        fn = lib().wfst_decode_lattice_arcs_batch
         ch = np.ascontiguousarray(channels, np.int32)
         offs = np.zeros(len(ch) + 1, np.int64)
         while True:
@@ -315,6 +313,31 @@ class WfstDecoder:
                 continue
             _check(rc, "wfst_decode_lattice_arcs_batch")
             return out[:offs[-1]].copy(), offs
+
+    def snapshot_lattice_arcs(self, snapshot: int, channels, out_device=None, copy: bool = True, cap: int = 1 << 20):
+        """Lattice arcs of a sealed snapshot: dict(starts, counts, total, block) and, with copy,
+        `records`: the snapshot's block on the host, or None when it went into the cuda tensor
+        `out_device`.  block = device address of the decoder's own block."""
+        ch = np.ascontiguousarray(channels, np.int32)
+        n = len(ch)
+        starts, counts = np.zeros(n, np.int64), np.zeros(n, np.int64)
+        total, block = C.c_int64(), C.c_void_p()
+        fn = lib().wfst_decode_snapshot_lattice_arcs
+        while True:
+            out, ptr, dev = None, None, 0
+            if copy and out_device is not None:
+                cap, ptr, dev = out_device.numel() * out_device.element_size() // LAT_DTYPE.itemsize, out_device.data_ptr(), 1
+            elif copy:
+                out = np.zeros(max(cap, 1), LAT_DTYPE)
+                ptr = out.ctypes.data
+            rc = fn(self.h, snapshot, ch.ctypes.data, n, starts.ctypes.data, counts.ctypes.data, ptr, cap, dev,
+                    C.byref(total), C.byref(block))
+            if rc == WFST_E_CAPACITY and out is not None:
+                cap = total.value
+                continue
+            _check(rc, "wfst_decode_snapshot_lattice_arcs")
+            return dict(starts=starts, counts=counts, total=total.value, block=block.value,
+                        records=None if out is None else out[:total.value].copy())
 
     def final_lattice(self, channel: int, use_final: bool = True, cap: int = 1 << 16):
         """(kept arcs as a structured array, info dict) of wfst_decode_final_lattice."""

@@ -61,6 +61,8 @@ struct wfst_decoder {
   int64_t next_snap_id = 1;
   struct SnapCall { int64_t id0; int32_t n_snaps, n_lanes; hipStream_t stream; };
   std::deque<SnapCall> snap_calls;      // the advance calls that seal snapshots, newest last
+  std::vector<int64_t> blk_ids;         // host mirror: snapshot id each block slot is assigned to
+  long long *d_ranges = nullptr;        // readout scratch [2 * max(num_channels, max_lanes) + 1]
   bool profiling = false;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
 };
@@ -244,6 +246,10 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
   if (c.aux_capacity == 0) c.aux_capacity = (int32_t)std::min<int64_t>(2ll * c.token_capacity, 1 << 29);
   if (c.history_capacity == 0) c.history_capacity = ((int64_t)c.max_frames + 1) * c.max_active;
   if (c.lattice_capacity == 0) c.lattice_capacity = 64ll * c.max_active;
+  if (c.snapshot_blocks < 0 || c.snapshot_block_capacity < 0) return WFST_E_INVALID_ARG;
+  if (!c.lattice_on) c.snapshot_blocks = 0;
+  if (c.snapshot_blocks > 0 && c.snapshot_block_capacity == 0)
+    c.snapshot_block_capacity = std::min<int64_t>(c.lattice_capacity, 4096ll * c.max_lanes);
   wfst_decoder *d = new (std::nothrow) wfst_decoder;
   if (!d) return WFST_E_DEVICE;
   d->graph = graph; d->cfg = c;
@@ -284,6 +290,14 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
   if (!rc && hipMemset(D.dbg, 0, 8 * (8 + 16384)) != hipSuccess) rc = WFST_E_DEVICE;
 #endif
   if (!rc) rc = dev_alloc(d, &d->d_offs, std::max(nc, nl) + 1);
+  if (!rc) rc = dev_alloc(d, &d->d_ranges, 2 * std::max(nc, nl) + 1);
+  D.n_blk = c.snapshot_blocks; D.blk_cap = c.snapshot_block_capacity;
+  if (!rc && D.n_blk > 0) {
+    rc = dev_alloc(d, &D.blk, (size_t)D.n_blk);
+    if (!rc) rc = dev_alloc(d, &D.blk_recs, (size_t)D.n_blk * (size_t)D.blk_cap);
+    if (!rc && hipMemset(D.blk, 0, sizeof(SnapBlock) * (size_t)D.n_blk) != hipSuccess) rc = WFST_E_DEVICE;
+    d->blk_ids.assign((size_t)D.n_blk, 0);
+  }
   if (!rc) {
     bool ok = hipMemset(D.chan, 0, sizeof(ChanState) * nc) == hipSuccess;
     for (int i = 0; ok && i < PARAM_RING; ++i)
@@ -380,7 +394,7 @@ static int advance_impl(wfst_decoder_t *d, const int32_t *channels, int32_t n_la
     int32_t longest = 0;
     for (int32_t i = 0; i < n_lanes; ++i) longest = std::max(longest, n_frames[i]);
     n_snaps = std::max(1, (longest + snapshot_every - 1) / snapshot_every);
-    if (n_snaps > SNAP_RING) return WFST_E_INVALID_ARG;
+    if (n_snaps > SNAP_RING || (d->dev.n_blk > 0 && n_snaps > d->dev.n_blk)) return WFST_E_INVALID_ARG;
   }
   const int64_t id0 = d->next_snap_id;
   std::vector<LaneParam> lp((size_t)n_lanes);
@@ -389,6 +403,11 @@ static int advance_impl(wfst_decoder_t *d, const int32_t *channels, int32_t n_la
     d->frames_fed[channels[i]] += n_frames[i];
   }
   d->last_stream = (hipStream_t)stream;
+  if (n_snaps > 0 && d->dev.n_blk > 0) {     // the blocks these snapshots will fill start empty
+    hipLaunchKernelGGL(k_reset_blocks, dim3((n_snaps + 63) / 64), dim3(64), 0, (hipStream_t)stream, d->dev, (long long)id0, n_snaps);
+    HIP_TRY(hipGetLastError());
+    for (int32_t j = 0; j < n_snaps; ++j) d->blk_ids[(size_t)((id0 + j) % d->dev.n_blk)] = id0 + j;
+  }
   rc = launch_lanes(d, lp, 0, (hipStream_t)stream);
   if (rc) return rc;
   if (n_snaps > 0) {
@@ -486,8 +505,12 @@ static int best_path_batch_impl(wfst_decoder_t *d, int64_t snap, const int32_t *
   rc = stage_channels(d, st, channels, n);
   if (rc) return rc;
   HIP_TRY(hipMemsetAsync(d->d_cnt, 0, sizeof(unsigned long long), st));
-  hipLaunchKernelGGL(k_best_path_words, dim3(n), dim3(64), 0, st, d->dev, (const int32_t *)d->d_chans, use_final, sn,
-                     (int32_t *)d->d_stage, words_cap, d->d_cnt, d->d_pathout);
+  if (snap > 0)      // beside a running decode kernel: one thread per channel
+    hipLaunchKernelGGL(k_best_path_words<1>, dim3((n + 63) / 64), dim3(64), 0, st, d->dev, (const int32_t *)d->d_chans, n,
+                       use_final, sn, (int32_t *)d->d_stage, words_cap, d->d_cnt, d->d_pathout);
+  else
+    hipLaunchKernelGGL(k_best_path_words<64>, dim3(n), dim3(64), 0, st, d->dev, (const int32_t *)d->d_chans, n,
+                       use_final, sn, (int32_t *)d->d_stage, words_cap, d->d_cnt, d->d_pathout);
   HIP_TRY(hipGetLastError());
   std::vector<PathOut> po((size_t)n);
   HIP_TRY(copy_sync_on(st, po.data(), d->d_pathout, sizeof(PathOut) * (size_t)n, hipMemcpyDeviceToHost));
@@ -601,17 +624,14 @@ int wfst_decode_lattice_arcs(wfst_decoder_t *d, int32_t channel, int32_t from_fr
   return 0;
 }
 
-static int lattice_arcs_batch_impl(wfst_decoder_t *d, int64_t snap, const int32_t *channels, int32_t n, wfst_lat_arc_t *out,
+int wfst_decode_lattice_arcs_batch(wfst_decoder_t *d, const int32_t *channels, int32_t n, wfst_lat_arc_t *out,
                                    int64_t cap, int64_t *offsets, int32_t out_is_device) {
   if (!d || n < 0 || cap < 0 || !offsets || (cap > 0 && !out)) return WFST_E_INVALID_ARG;
   offsets[0] = 0;
   if (n == 0) return 0;
   int rc = check_channels(d, channels, n, true);
   if (rc) return rc;
-  hipStream_t st = nullptr;
-  rc = readout_stream(d, snap, &st);
-  if (rc) return rc;
-  const long long sn = snap > 0 ? (long long)snap : 0ll;
+  hipStream_t st = d->last_stream;
   rc = stage_channels(d, st, channels, n);
   if (rc) return rc;
   LatRec *dst = (LatRec *)out;
@@ -623,7 +643,7 @@ static int lattice_arcs_batch_impl(wfst_decoder_t *d, int64_t snap, const int32_
   }
   // offsets, copy and reset are queued back to back; the copy and the reset check the capacity
   // on the device, so the host waits only once
-  hipLaunchKernelGGL(k_lattice_offsets, dim3(1), dim3(1024), 0, st, d->dev, (const int32_t *)d->d_chans, n, sn, d->d_offs);
+  hipLaunchKernelGGL(k_lattice_offsets, dim3(1), dim3(1024), 0, st, d->dev, (const int32_t *)d->d_chans, n, d->d_offs);
   hipLaunchKernelGGL(k_export_lattice_batch, dim3(n, 8), dim3(256), 0, st, d->dev, (const int32_t *)d->d_chans, n,
                      (const long long *)d->d_offs, dst, (long long)cap);
   hipLaunchKernelGGL(k_reset_lattice_batch, dim3((n + 255) / 256), dim3(256), 0, st, d->dev, (const int32_t *)d->d_chans, n,
@@ -637,15 +657,38 @@ static int lattice_arcs_batch_impl(wfst_decoder_t *d, int64_t snap, const int32_
   return 0;
 }
 
-int wfst_decode_lattice_arcs_batch(wfst_decoder_t *d, const int32_t *channels, int32_t n, wfst_lat_arc_t *out,
-                                   int64_t cap, int64_t *offsets, int32_t out_is_device) {
-  return lattice_arcs_batch_impl(d, 0, channels, n, out, cap, offsets, out_is_device);
-}
-
-int wfst_decode_snapshot_lattice_arcs_batch(wfst_decoder_t *d, int64_t snapshot_id, const int32_t *channels, int32_t n,
-                                            wfst_lat_arc_t *out, int64_t cap, int64_t *offsets, int32_t out_is_device) {
-  if (snapshot_id < 1) return WFST_E_INVALID_ARG;
-  return lattice_arcs_batch_impl(d, snapshot_id, channels, n, out, cap, offsets, out_is_device);
+int wfst_decode_snapshot_lattice_arcs(wfst_decoder_t *d, int64_t snapshot_id, const int32_t *channels, int32_t n,
+                                      int64_t *starts, int64_t *counts, wfst_lat_arc_t *out, int64_t cap,
+                                      int32_t out_is_device, int64_t *total, const wfst_lat_arc_t **block) {
+  if (!d || snapshot_id < 1 || n < 0 || cap < 0 || !total || (n > 0 && (!starts || !counts))) return WFST_E_INVALID_ARG;
+  if (d->dev.n_blk <= 0) return WFST_E_INVALID_ARG;              // the decoder was created without snapshot blocks
+  int rc = check_channels(d, channels, n, true);
+  if (rc) return rc;
+  hipStream_t st = nullptr;
+  rc = readout_stream(d, snapshot_id, &st);
+  if (rc) return rc;
+  const size_t slot = (size_t)(snapshot_id % d->dev.n_blk);
+  if (d->blk_ids[slot] != snapshot_id) return WFST_E_NOT_INIT;   // its block has been given to a later snapshot
+  if (n > 0) {
+    rc = stage_channels(d, st, channels, n);
+    if (rc) return rc;
+  }
+  hipLaunchKernelGGL(k_snapshot_ranges, dim3((std::max(n, 1) + 255) / 256), dim3(256), 0, st, d->dev, (const int32_t *)d->d_chans, n,
+                     (long long)snapshot_id, d->d_ranges);
+  HIP_TRY(hipGetLastError());
+  std::vector<long long> r(2 * (size_t)n + 1);
+  HIP_TRY(copy_sync_on(st, r.data(), d->d_ranges, sizeof(long long) * r.size(), hipMemcpyDeviceToHost));
+  if (r[2 * (size_t)n] < 0) return WFST_E_NOT_INIT;
+  for (int32_t i = 0; i < n; ++i) { starts[i] = r[2 * (size_t)i]; counts[i] = r[2 * (size_t)i + 1]; }
+  *total = r[2 * (size_t)n];
+  const LatRec *src = d->dev.blk_recs + slot * (size_t)d->dev.blk_cap;
+  if (block) *block = (const wfst_lat_arc_t *)src;
+  if (out) {
+    if (*total > cap) return WFST_E_CAPACITY;
+    if (*total > 0)
+      HIP_TRY(copy_sync_on(st, out, src, sizeof(LatRec) * (size_t)*total, out_is_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost));
+  }
+  return 0;
 }
 
 int wfst_decode_final_lattice(wfst_decoder_t *d, int32_t channel, int32_t use_final, wfst_lat_arc_t *out, int64_t cap,

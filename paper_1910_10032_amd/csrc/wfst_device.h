@@ -73,9 +73,9 @@ struct ChanState {
   int32_t num_frames;        // token frames written (frame 0 comes from init)
   long long hist_used;       // tokens in the history
   // Lattice records of a channel live in a ring of lat_cap records: record number v (counted
-  // from init) sits at v % lat_cap.  Records [lat_head, lat_total) have not been handed out.
-  // lat_head belongs to the readouts (they may run while the channel is being decoded), every
-  // other field to the lane kernel.
+  // from init) sits at v % lat_cap.  Records [lat_head, lat_total) have not been handed out:
+  // a live drain hands them to the caller, a lane that seals a snapshot moves them into the
+  // snapshot's block.
   long long lat_head;
   long long lat_total;       // lattice records produced since init
   long long arcs_expanded;
@@ -91,7 +91,11 @@ struct __align__(16) ChanSnap {
   long long lat_total;       // lattice records produced up to the boundary
   long long hist_used;
   int32_t status, num_frames;
+  long long blk_start, blk_count;   // where the lane put the channel's pending lattice records in the snapshot's block
 };
+// Lattice records of one snapshot, all lanes together, in the form handed to the caller.
+// Each lane reserves its range with one compare-and-swap on `used`.
+struct SnapBlock { unsigned long long used; long long id; };
 
 struct LaneParam {
   const float *ll;           // device rows of this lane
@@ -106,6 +110,10 @@ struct DecDev {
   ChanState *chan;
   ChanSnap *snap;            // [num_channels][SNAP_RING]
   long long *lane_sealed;    // [max_lanes] pinned host memory: id of the last snapshot a lane sealed
+  SnapBlock *blk;            // [n_blk] snapshot id -> block id % n_blk
+  LatRec *blk_recs;          // [n_blk][blk_cap]
+  long long blk_cap;
+  int32_t n_blk, pad0;
   long long *frame_off;      // [num_channels][max_frames + 2] start of each frame in hist
   HTok *hist;                // [num_channels][hist_cap]
   LatInt *lat;               // [num_channels][lat_cap]

@@ -123,6 +123,7 @@ struct LaneShared {
   int status, nf, max_pre, max_post, iters_max, n_in;
   long long in_off, hist_used, lat_room, lat_total, arcs_expanded;
   long long lat_pos;           // ring position of record number lat_total
+  long long lat_head, lat_head_pos, blk_pos;   // first record not handed out, its ring position; seal scratch
 #ifdef WFST_PHASE_TIMING
   unsigned long long ph[16], tlast, dbg_tok, dbg_iters, dbg_arcs;
 #endif
@@ -650,12 +651,15 @@ __global__ void __launch_bounds__(NT, NT / 128) k_advance(DecDev D, const LanePa
   if (tid == 0) {
     if (is_init) {
       S.status = 0; S.nf = 0; S.hist_used = 0; S.lat_room = D.lat_cap; S.lat_pos = 0; S.lat_total = 0; S.arcs_expanded = 0;
+      S.lat_head = 0; S.lat_head_pos = 0;
       S.max_pre = 0; S.max_post = 0; S.iters_max = 0;
       foff[0] = 0;
     } else {
       S.status = cs->status; S.nf = cs->num_frames; S.hist_used = cs->hist_used;
-      S.lat_room = D.lat_cap - (cs->lat_total - (long long)ld64((const unsigned long long *)&cs->lat_head));
+      S.lat_head = cs->lat_head;
+      S.lat_room = D.lat_cap - (cs->lat_total - S.lat_head);
       S.lat_pos = cs->lat_total % D.lat_cap;
+      S.lat_head_pos = S.lat_head % D.lat_cap;
       S.lat_total = cs->lat_total; S.arcs_expanded = cs->arcs_expanded; S.max_pre = cs->max_pre;
       S.max_post = cs->max_post; S.iters_max = cs->closure_iters_max;
     }
@@ -668,55 +672,104 @@ __global__ void __launch_bounds__(NT, NT / 128) k_advance(DecDev D, const LanePa
 #endif
   }
   __syncthreads();
-  // Seal the lane's state as snapshot number `j` of this call: everything the workgroup has
-  // written so far is made visible to the whole system, then the snapshot entry and the
-  // lane's progress word.  Readouts of the snapshot start only after the host has seen the
-  // progress words of all lanes, so they never wait inside a kernel.
+  // Seal the lane's state as the next snapshot of this call.  With snapshot blocks the lattice
+  // records not handed out yet move into the snapshot's block, in the caller's form (the lane
+  // reserves its range with one compare-and-swap; the ring is empty afterwards).  Then
+  // everything the workgroup has written is made visible to the whole system, then the
+  // snapshot entry and the lane's progress word.  Readouts of the snapshot start only after
+  // the host has seen the progress words of all lanes, so nothing ever waits inside a kernel.
   int n_sealed = 0;
   auto seal = [&]() {
     __syncthreads();                                  // all waves' stores have been issued and acknowledged
+    const long long id = lp.snap_id0 + n_sealed;
+    long long blk_start = 0, blk_count = 0;
+    if (D.n_blk > 0 && D.lattice_on) {
+      const int slot = (int)(id % D.n_blk);
+      const long long n = S.lat_total - S.lat_head;
+      if (tid == 0) {
+        unsigned long long *used = &D.blk[slot].used;
+        unsigned long long old = ld64(used);
+        long long pos = -1;
+        while ((long long)old + n <= D.blk_cap) {     // every failed swap means another lane got its range
+          const unsigned long long seen = atomicCAS(used, old, old + (unsigned long long)n);
+          if (seen == old) { pos = (long long)old; break; }
+          old = seen;
+        }
+        if (pos < 0 && S.status == 0) S.status = E_LATTICE_OVERFLOW;
+        S.blk_pos = pos;
+      }
+      __syncthreads();
+      const long long pos = S.blk_pos;
+      if (pos >= 0) {
+        LatRec *out = D.blk_recs + (size_t)slot * (size_t)D.blk_cap + (size_t)pos;
+        const long long first = S.lat_head_pos;
+        constexpr int U = 8;                            // records per thread in flight: the arc-id gathers are HBM round trips
+        for (long long i0 = tid; i0 < n; i0 += (long long)NT * U) {
+          LatInt r[U];
+          uint32_t arc_id[U];
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            const long long i = i0 + (long long)u * NT;
+            if (i < n) r[u] = lat[first + i < D.lat_cap ? first + i : first + i - D.lat_cap];
+          }
+#pragma unroll
+          for (int u = 0; u < U; ++u) if (i0 + (long long)u * NT < n) arc_id[u] = D.g.orig[r[u].arc];
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            const long long i = i0 + (long long)u * NT;
+            if (i < n) out[i] = LatRec{r[u].frame, arc_id[u], r[u].extra};
+          }
+        }
+        blk_start = pos; blk_count = n;
+      }
+      __syncthreads();
+      if (tid == 0) { S.lat_head = S.lat_total; S.lat_head_pos = S.lat_pos; S.lat_room = D.lat_cap; }
+    }
     if (tid == 0) {
-      const long long id = lp.snap_id0 + n_sealed;
       ChanSnap *sp = D.snap + (size_t)lp.chan * SNAP_RING + (size_t)(id % SNAP_RING);
       sp->lat_total = S.lat_total; sp->hist_used = S.hist_used; sp->status = S.status; sp->num_frames = S.nf;
+      sp->blk_start = blk_start; sp->blk_count = blk_count;
       sp->id = id;
-      // space freed by drains that ran beside this call
-      S.lat_room = D.lat_cap - (S.lat_total - (long long)ld64((const unsigned long long *)&cs->lat_head));
       __hip_atomic_store(D.lane_sealed + blockIdx.x, id, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     }
     ++n_sealed;
   };
   const int nframes = is_init ? 1 : lp.n_frames;
+  const int n_snaps = is_init ? 0 : lp.n_snaps;
   int until_seal = (!is_init && lp.snap_every > 0) ? lp.snap_every : 0x7FFFFFFF;
-  for (int f = 0; f < nframes; ++f) {
-    if (S.status != 0) break;
-    const float *ll = is_init ? nullptr : lp.ll + (size_t)f * (size_t)lp.stride;
-    const int nf = S.nf;
-    bool small = is_init != 0;
-    if (!small) small = S.n_in <= LDS_NIN_MAX;
-    bool done = false;
-    if (small) done = lane_frame<NT, true>(D, S, lp, ll, is_init != 0, slots, queue, aux, dkey, dslot, foff, hist, lat);
-    if (!done) {
+  for (int f = 0;;) {
+    const bool more = f < nframes && S.status == 0;
+    if (more) {
+      const float *ll = is_init ? nullptr : lp.ll + (size_t)f * (size_t)lp.stride;
+      bool small = is_init != 0;
+      if (!small) small = S.n_in <= LDS_NIN_MAX;
+      bool done = false;
+      if (small) done = lane_frame<NT, true>(D, S, lp, ll, is_init != 0, slots, queue, aux, dkey, dslot, foff, hist, lat);
+      if (!done) {
 #ifdef WFST_PHASE_TIMING
-      if (tid == 0 && small) S.ph[6] += 1;
+        if (tid == 0 && small) S.ph[6] += 1;
 #endif
-      lane_frame<NT, false>(D, S, lp, ll, is_init != 0, slots, queue, aux, dkey, dslot, foff, hist, lat);
-    }
+        lane_frame<NT, false>(D, S, lp, ll, is_init != 0, slots, queue, aux, dkey, dslot, foff, hist, lat);
+      }
 #ifdef WFST_PHASE_TIMING
-    if (tid == 0) S.ph[5] += 1;
+      if (tid == 0) S.ph[5] += 1;
 #endif
-    if (--until_seal == 0) {
-      if (n_sealed < lp.n_snaps) seal();
+      ++f;
+      if (--until_seal != 0) continue;
       until_seal = lp.snap_every;
     }
+    // a snapshot boundary - or the lane has run out of frames or stopped: it seals the
+    // snapshots still due in the state it is in
+    if (n_sealed >= n_snaps) { if (more) continue; break; }
+    seal();
   }
-  if (!is_init) while (n_sealed < lp.n_snaps) seal();  // a lane that ran out of frames, or stopped, seals the rest as it is
   __syncthreads();
   if (tid == 0) {
     cs->status = S.status; cs->num_frames = S.nf; cs->hist_used = S.hist_used;
     cs->lat_total = S.lat_total; cs->arcs_expanded = S.arcs_expanded; cs->max_pre = S.max_pre;
     cs->max_post = S.max_post; cs->closure_iters_max = S.iters_max;
-    if (is_init) { cs->path_nf = 0; cs->lat_head = 0; }
+    if (is_init) cs->path_nf = 0;
+    cs->lat_head = S.lat_head;
 #ifdef WFST_PHASE_TIMING
     if (D.dbg) {
       for (int k = 0; k < 8; ++k) atomicAdd(D.dbg + k, S.ph[k]);
@@ -757,8 +810,10 @@ __device__ __forceinline__ ChanView chan_view(const DecDev &D, int ch, long long
   return ChanView{sp->status, sp->num_frames, sp->hist_used, sp->lat_total};
 }
 
+// W threads work on one channel (a whole wave, or a single thread).
+template <int W>
 __device__ __forceinline__ bool path_start(const DecDev &D, int ch, int use_final, const ChanView &cv, PathOut &po, int &F, int &cur) {
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x % W;
   const long long *foff = D.frame_off + (size_t)ch * (size_t)(D.max_frames + 2);
   const HTok *hist = D.hist + (size_t)ch * (size_t)D.hist_cap;
   const uint32_t *rec = D.g.rec;
@@ -768,7 +823,7 @@ __device__ __forceinline__ bool path_start(const DecDev &D, int ch, int use_fina
   const long long o = foff[F];
   const int n = (int)(foff[F + 1] - o);
   unsigned long long bf = ~0ull, bn = ~0ull; int bfi = -1, bni = -1;
-  for (int i = lane; i < n; i += 64) {
+  for (int i = lane; i < n; i += W) {
     const HTok t = hist[o + i];
     const uint32_t h = t.handle & HMASK;
     const unsigned long long kn = pack(okey(t.cost), h);
@@ -781,7 +836,7 @@ __device__ __forceinline__ bool path_start(const DecDev &D, int ch, int use_fina
       }
     }
   }
-  for (int d = 32; d; d >>= 1) {
+  for (int d = W / 2; d; d >>= 1) {
     unsigned long long o2 = __shfl_xor(bn, d, 64); int i2 = __shfl_xor(bni, d, 64);
     if (o2 < bn) { bn = o2; bni = i2; }
     o2 = __shfl_xor(bf, d, 64); i2 = __shfl_xor(bfi, d, 64);
@@ -805,7 +860,7 @@ __global__ void __launch_bounds__(64) k_best_path(DecDev D, const int32_t *chans
   PathOut po{0, 0, 0, 0, 0.f, 0, 0};
   int F = 0, cur = 0;
   const ChanView cv = chan_view(D, ch, snap_id);
-  const bool ok = path_start(D, ch, use_final, cv, po, F, cur);
+  const bool ok = path_start<64>(D, ch, use_final, cv, po, F, cur);
   if (threadIdx.x != 0) return;
   if (!ok) { out[blockIdx.x] = po; return; }
   int32_t *wout = words ? words + (size_t)blockIdx.x * words_cap : nullptr;
@@ -835,25 +890,33 @@ __global__ void __launch_bounds__(64) k_best_path(DecDev D, const int32_t *chans
 // a new trace walks back only until it meets the remembered path (a chunk of frames plus the
 // distance to the merge point, not the whole utterance) and splices the remembered prefix.
 // Words of all channels are packed into `words` at po.word_off (allotted with one atomic add).
-__global__ void __launch_bounds__(64) k_best_path_words(DecDev D, const int32_t *chans, int use_final, long long snap_id, int32_t *words,
-                                                        int words_cap, unsigned long long *words_used, PathOut *out) {
-  const int ch = chans[blockIdx.x];
-  const int lane = threadIdx.x;
+// W = 64: one wave per channel (fastest when the GPU is otherwise idle).  W = 1: one thread
+// per channel, eight waves for 500 channels, which still find room beside a running decode
+// kernel whose workgroups hold nearly all wave slots.
+template <int W>
+__global__ void __launch_bounds__(64) k_best_path_words(DecDev D, const int32_t *chans, int n_ch, int use_final, long long snap_id,
+                                                        int32_t *words, int words_cap, unsigned long long *words_used, PathOut *out) {
+  const int gi = (int)((blockIdx.x * blockDim.x + threadIdx.x) / W);      // channel of this thread group
+  if (gi >= n_ch) return;                                                // (W = 64: one group per block)
+  const int ch = chans[gi];
+  const int lane = threadIdx.x % W;
   ChanState *cs = D.chan + ch;
   const long long *foff = D.frame_off + (size_t)ch * (size_t)(D.max_frames + 2);
   const HTok *hist = D.hist + (size_t)ch * (size_t)D.hist_cap;
   int32_t *entry = D.pc_entry + (size_t)ch * (size_t)(D.max_frames + 2);
   int32_t *wcount = D.pc_wcount + (size_t)ch * (size_t)(D.max_frames + 2);
   int32_t *cw = D.pc_words + (size_t)ch * (size_t)D.pc_wcap;
-  __shared__ int sh[4];                      // status, total words, merge frame, F
+  __shared__ int sh[4];                      // status, total words, merge frame, new words (W > 1)
+  __shared__ long long sh_off;
   PathOut po{0, 0, 0, 0, 0.f, 0, 0};
   int F = 0, cur = 0;
   const ChanView cv = chan_view(D, ch, snap_id);
-  const bool ok = path_start(D, ch, use_final, cv, po, F, cur);
-  if (!ok) { if (lane == 0) out[blockIdx.x] = po; return; }
+  const bool ok = path_start<W>(D, ch, use_final, cv, po, F, cur);
+  if (!ok) { if (lane == 0) out[gi] = po; return; }
+  int status = 0, total = 0, merge_f = 0, k = 0;
   if (lane == 0) {
     const int cached_nf = cs->path_nf;
-    int f = F, k = 0, base = 0, merge_f = 0, status = 0;
+    int f = F, base = 0;
     const long long max_steps = cv.hist_used + 1;
     // the token of the next step is fetched while this step's word label is still on its way
     auto in_frame = [&](int ff, int c) { return ff >= 0 && c >= 0 && (long long)c < foff[ff + 1] - foff[ff]; };
@@ -871,41 +934,47 @@ __global__ void __launch_bounds__(64) k_best_path_words(DecDev D, const int32_t 
       const int ncur = is_entry ? (int)t.prev : (int)(t.prev & ~PREV_SAME);
       const int nf = is_entry ? f - 1 : f;
       HTok tn{};
-      const bool ok = in_frame(nf, ncur);
-      if (ok) tn = hist[foff[nf] + ncur];
+      const bool ok2 = in_frame(nf, ncur);
+      if (ok2) tn = hist[foff[nf] + ncur];
       if (w != 0) {
         if (k < D.pc_wcap) cw[D.pc_wcap - 1 - k] = w;
         ++k;
       }
-      if (!ok) { status = E_BROKEN_TRACE; break; }
+      if (!ok2) { status = E_BROKEN_TRACE; break; }
       cur = ncur; f = nf; t = tn;
     }
     if (status == 0 && (long long)base + 2ll * k > (long long)D.pc_wcap) status = E_CAPACITY;
-    sh[0] = status; sh[1] = base + k; sh[2] = merge_f; sh[3] = k;
+    total = base + k;
   }
-  __syncthreads();
-  const int status = sh[0], total = sh[1], merge_f = sh[2], k = sh[3];
+  if constexpr (W > 1) {
+    if (lane == 0) { sh[0] = status; sh[1] = total; sh[2] = merge_f; sh[3] = k; }
+    __syncthreads();
+    status = sh[0]; total = sh[1]; merge_f = sh[2]; k = sh[3];
+  }
   if (status != 0) {
-    if (lane == 0) { cs->path_nf = 0; po.status = status; po.n_words = total; out[blockIdx.x] = po; }
+    if (lane == 0) { cs->path_nf = 0; po.status = status; po.n_words = total; out[gi] = po; }
     return;
   }
-  for (int f = merge_f + 1 + lane; f <= F; f += 64) wcount[f] = total - wcount[f];
+  for (int f = merge_f + 1 + lane; f <= F; f += W) wcount[f] = total - wcount[f];
   const int base = total - k;
-  for (int j = lane; j < k; j += 64) cw[base + j] = cw[D.pc_wcap - k + j];
-  __syncthreads();
+  for (int j = lane; j < k; j += W) cw[base + j] = cw[D.pc_wcap - k + j];
+  if constexpr (W > 1) __syncthreads();
+  long long off = 0;
   if (lane == 0) {
     cs->path_nf = F + 1;
     po.n_words = total;
     if (total > words_cap) po.status = E_CAPACITY;
     else po.word_off = (long long)atomicAdd(words_used, (unsigned long long)total);
-    sh[0] = po.status;
-    *(long long *)&sh[2] = po.word_off;
-    out[blockIdx.x] = po;
+    off = po.word_off;
+    out[gi] = po;
   }
-  __syncthreads();
-  if (sh[0] != 0) return;
-  const long long off = *(long long *)&sh[2];
-  for (int j = lane; j < total; j += 64) words[off + j] = cw[j];
+  if constexpr (W > 1) {
+    if (lane == 0) { sh[0] = po.status; sh_off = off; }
+    __syncthreads();
+    po.status = sh[0]; off = sh_off;
+  }
+  if (po.status != 0) return;
+  for (int j = lane; j < total; j += W) words[off + j] = cw[j];
 }
 
 // Tokens of one frame in the public form: state id and caller's arc id.
@@ -931,13 +1000,11 @@ __global__ void k_export_lattice(DecDev D, int ch, long long start, long long n,
     if ((long long)p < cap) out[p] = LatRec{r.frame, D.g.orig[r.arc], r.extra};
   }
 }
-// Records a readout hands out: those not handed out yet, up to the live end or the
-// snapshot's.  A channel stopped by an overflow hands out nothing.
-__device__ __forceinline__ long long lattice_pending(const DecDev &D, int ch, long long snap_id) {
-  const ChanView cv = chan_view(D, ch, snap_id);
-  const bool readable = cv.status == 0 || cv.status == E_DEAD_CHANNEL || cv.status == E_NAN_INPUT;
-  if (!readable) return 0;
-  return max(0ll, cv.lat_total - D.chan[ch].lat_head);
+// Records a live drain hands out.  A channel stopped by an overflow hands out nothing.
+__device__ __forceinline__ long long lattice_pending(const DecDev &D, int ch) {
+  const ChanState *cs = D.chan + ch;
+  const bool readable = cs->status == 0 || cs->status == E_DEAD_CHANNEL || cs->status == E_NAN_INPUT;
+  return readable ? cs->lat_total - cs->lat_head : 0;
 }
 __global__ void k_reset_lattice(DecDev D, int ch) { D.chan[ch].lat_head = D.chan[ch].lat_total; }
 
@@ -945,14 +1012,14 @@ __global__ void k_reset_lattice(DecDev D, int ch) { D.chan[ch].lat_head = D.chan
 // grid.y = slices of that channel's buffer), then the reset.
 // offs[0..n]: exclusive prefix sums of the buffered record counts of the listed channels
 // (channels stopped by an overflow count as empty).  One block.
-__global__ void __launch_bounds__(1024) k_lattice_offsets(DecDev D, const int32_t *chans, int n, long long snap_id, long long *offs) {
+__global__ void __launch_bounds__(1024) k_lattice_offsets(DecDev D, const int32_t *chans, int n, long long *offs) {
   __shared__ long long part[1024];
   const int tid = threadIdx.x;
   const int per = (n + 1023) / 1024;
   const int b = tid * per, e = min(n, b + per);
   long long sum = 0;
   for (int i = b; i < e; ++i) {
-    sum += lattice_pending(D, chans[i], snap_id);
+    sum += lattice_pending(D, chans[i]);
   }
   part[tid] = sum;
   __syncthreads();
@@ -965,7 +1032,7 @@ __global__ void __launch_bounds__(1024) k_lattice_offsets(DecDev D, const int32_
   long long run = part[tid] - sum;
   for (int i = b; i < e; ++i) {
     offs[i] = run;
-    run += lattice_pending(D, chans[i], snap_id);
+    run += lattice_pending(D, chans[i]);
   }
   if (tid == 1023) offs[n] = part[1023];
 }
@@ -985,6 +1052,28 @@ __global__ void k_reset_lattice_batch(DecDev D, const int32_t *chans, int n, con
   if (offs[n] > cap) return;
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) D.chan[chans[i]].lat_head += offs[i + 1] - offs[i];
+}
+
+// Snapshot blocks: the slots of a call's snapshots are emptied before its lanes start.
+__global__ void k_reset_blocks(DecDev D, long long id0, int n) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < n) D.blk[(id0 + j) % D.n_blk] = SnapBlock{0ull, id0 + j};
+}
+// Where each listed channel's lattice records sit in the block of snapshot `id`:
+// out[2i] = start, out[2i+1] = count (0, 0 for a channel without that snapshot);
+// out[2n] = records in the block, all lanes together.
+__global__ void k_snapshot_ranges(DecDev D, const int32_t *chans, int n, long long id, long long *out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) {
+    const ChanSnap *sp = D.snap + (size_t)chans[i] * SNAP_RING + (size_t)(id % SNAP_RING);
+    const bool have = sp->id == id;
+    out[2 * i] = have ? sp->blk_start : 0;
+    out[2 * i + 1] = have ? sp->blk_count : 0;
+  }
+  if (i == 0) {
+    const SnapBlock b = D.blk[id % D.n_blk];
+    out[2 * n] = b.id == id ? (long long)b.used : -1;
+  }
 }
 
 // ---- final lattice -------------------------------------------------------------------------

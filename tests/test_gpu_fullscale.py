@@ -13,7 +13,7 @@ from gpu_compare import check_final_lattice, sorted_tokens
 pytestmark = pytest.mark.gpu
 
 
-def decode_and_compare(cfg, sample, token_capacity, history_capacity, lattice_capacity, frame_step=1):
+def decode_and_compare(cfg, sample, token_capacity, history_capacity, lattice_capacity, frame_step=1, **kw):
     import torch
 
     from paper_1910_10032_amd import binding as B
@@ -25,7 +25,7 @@ def decode_and_compare(cfg, sample, token_capacity, history_capacity, lattice_ca
     T = int(lens.max())
     dec = B.WfstDecoder(graph, cfg.beam, cfg.lattice_beam, cfg.max_active, num_channels=n_ch, max_lanes=n_ch,
                         max_frames=T, token_capacity=token_capacity, history_capacity=history_capacity,
-                        lattice_capacity=lattice_capacity)
+                        lattice_capacity=lattice_capacity, **kw)
     # scores of all streams, ragged, in one device buffer
     starts = np.concatenate([[0], np.cumsum(lens)])
     scores = torch.empty((int(starts[-1]), P), dtype=torch.float32, device="cuda")
@@ -50,9 +50,10 @@ def decode_and_compare(cfg, sample, token_capacity, history_capacity, lattice_ca
         for j in range(count):
             paths = dec.best_path_batch(chans, use_final=False, words_cap=1024, raw=True, snapshot=first + j)
             assert (paths[4] == 0).all()
-            recs, offs = dec.lattice_arcs_batch(chans, snapshot=first + j)
+            r = dec.snapshot_lattice_arcs(first + j, chans)
+            assert r["counts"].sum() == r["total"]
             for s in sample:
-                lat[s].append(recs[offs[s]:offs[s + 1]])
+                lat[s].append(r["records"][r["starts"][s]:r["starts"][s] + r["counts"][s]])
                 partial[s].append(paths[0][s, :paths[1][s]].copy())
     else:
         dec.advance_ptrs(chans, (base + starts[:-1] * P * 4).astype(np.uint64), strides, lens.astype(np.int32), stream)
@@ -120,7 +121,7 @@ def decode_and_compare(cfg, sample, token_capacity, history_capacity, lattice_ca
 def test_config3_online_500_channels():
     cfg = synth.configs()[3]
     decode_and_compare(cfg, sample=[0, 137, 499], token_capacity=16384, history_capacity=2_500_000,
-                       lattice_capacity=1_000_000)
+                       lattice_capacity=400_000, snapshot_blocks=40, snapshot_block_capacity=16_000 * cfg.n_streams)
 
 
 def test_config2_offline_ragged_batch():

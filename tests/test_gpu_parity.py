@@ -358,30 +358,45 @@ def _check_paths(got, ods_at, use_final, label):
         assert r["reached_final"] == want["reached_final"], f"{label} ch {ch}"
 
 
+def _check_snapshot_lattice(dec, snap, chans, want_of, label):
+    """The snapshot's block: every listed channel's range must hold exactly the records
+    want_of(ch) = (frames, arcs, extras); ranges must not overlap and must fill the block."""
+    r = dec.snapshot_lattice_arcs(snap, chans)
+    covered = 0
+    spans = []
+    for i, ch in enumerate(chans):
+        a, c = int(r["starts"][i]), int(r["counts"][i])
+        _assert_records(r["records"][a:a + c], want_of(ch), f"{label} ch {ch}")
+        spans.append((a, a + c))
+        covered += c
+    spans.sort()
+    assert all(spans[i][1] <= spans[i + 1][0] for i in range(len(spans) - 1)), f"{label}: ranges overlap"
+    return r, covered
+
+
 def test_snapshots_sealed_inside_one_call(torch_cuda, B):
     """One advance call over the whole (ragged) utterances with a snapshot every 10 frames: the
-    lanes seal their state at each boundary and go on; best paths and lattice records of every
-    snapshot, read while the call may still be running, must be the checker's at that frame.
-    One channel skips drains, which must delay its records, not lose them; a lane shorter
-    than the call seals the remaining snapshots at its end state."""
+    lanes seal their state at each boundary, move their pending lattice records into the
+    snapshot's block and go on; best paths and lattice records of every snapshot, read while
+    the call may still be running, must be the checker's at that frame.  A lane shorter than
+    the call seals the remaining snapshots at its end state (with no new records)."""
     torch = torch_cuda
     c = synth.configs()[0]
     g = synth.make_graph(c.graph)
     lens, chunk = [160, 160, 95, 160], 10
     n, T = len(lens), max(lens)
     rows = [c.loglikes(s, 0, lens[s]) for s in range(n)]
-    gg = B.WfstGraph(g)
-    dec = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=n, max_lanes=n, max_frames=T,
-                        lattice_capacity=300_000)
-    chans = list(range(n))
-    dec.init_channels(chans)
-    dev = [torch.from_numpy(r).cuda() for r in rows]
     og = oracle.OracleGraph(g)
     ods = [oracle.OracleDecoder(og, c.beam, c.lattice_beam, c.max_active) for _ in range(n)]
     for od, r in zip(ods, rows):
         od.advance(r)
+    gg = B.WfstGraph(g)
+    dec = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=n, max_lanes=n, max_frames=T,
+                        lattice_capacity=40_000, snapshot_blocks=T // chunk, snapshot_block_capacity=60_000)
+    chans = list(range(n))
+    dec.init_channels(chans)
+    dev = [torch.from_numpy(r).cuda() for r in rows]
     step = [oracle.OracleDecoder(og, c.beam, c.lattice_beam, c.max_active) for _ in range(n)]
-    drained_to = [0] * n
     with torch.cuda.stream(torch.cuda.Stream()):
         first, count = dec.advance(chans, dev, snapshot_every=chunk)
     assert count == T // chunk and first >= 1
@@ -390,25 +405,23 @@ def test_snapshots_sealed_inside_one_call(torch_cuda, B):
             if len(r[j * chunk:(j + 1) * chunk]):             # nothing once the stream has ended
                 od.advance(r[j * chunk:(j + 1) * chunk])
         _check_paths(dec.best_path_batch(chans, use_final=(j % 2 == 0), snapshot=first + j), step, j % 2 == 0, f"snapshot {j}")
-        listed = [ch for ch in chans if not (ch == 3 and j % 3 != 2)]   # channel 3 is drained every third snapshot
-        recs, offs = dec.lattice_arcs_batch(listed, snapshot=first + j)
-        for i, ch in enumerate(listed):
-            end = min((j + 1) * chunk, lens[ch]) + 1
-            _assert_records(recs[offs[i]:offs[i + 1]], _oracle_lattice_of_frames(ods[ch], drained_to[ch], end), f"snapshot {j} ch {ch}")
-            drained_to[ch] = end
+        lo = lambda ch: min(0 if j == 0 else j * chunk + 1, lens[ch] + 1)
+        hi = lambda ch: min((j + 1) * chunk, lens[ch]) + 1
+        r, covered = _check_snapshot_lattice(dec, first + j, chans, lambda ch: _oracle_lattice_of_frames(ods[ch], lo(ch), hi(ch)),
+                                             f"snapshot {j}")
+        assert covered == r["total"]
     torch.cuda.synchronize()
-    # what is left (channel 3: the frames after its last drain) comes out of the live drain
-    recs, offs = dec.lattice_arcs_batch(chans)
+    recs, offs = dec.lattice_arcs_batch(chans)                 # everything has been handed over already
+    assert offs[-1] == 0
     for ch in chans:
-        _assert_records(recs[offs[ch]:offs[ch + 1]], _oracle_lattice_of_frames(ods[ch], drained_to[ch], T + 1), f"rest ch {ch}")
-    for ch in chans:
+        assert dec.stats(ch)["lattice_arcs"] == len(ods[ch].lattice()[0])
         compare_channel(dec, ch, ods[ch], label=f"snapshot-flow ch{ch}", lattice=False)
 
 
 def test_snapshot_pipeline_over_calls_wraps_the_lattice_ring(torch_cuda, B):
     """Chunk k + 1 is queued before chunk k's snapshot is read, call after call; the lattice
-    ring is a few chunks long, so it wraps many times and space must come back from the
-    drains that run beside the decoding."""
+    ring holds little more than one chunk, so it wraps many times; the blocks are reused
+    round-robin."""
     torch = torch_cuda
     c = synth.configs()[0]
     g = synth.make_graph(c.graph)
@@ -421,7 +434,7 @@ def test_snapshot_pipeline_over_calls_wraps_the_lattice_ring(torch_cuda, B):
     per_chunk = max(len(_oracle_lattice_of_frames(od, f0 + 1, f0 + chunk + 1)[0]) for od in ods for f0 in range(0, T, chunk))
     gg = B.WfstGraph(g)
     dec = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=n, max_lanes=n, max_frames=T,
-                        lattice_capacity=int(3.5 * per_chunk))
+                        lattice_capacity=int(1.4 * per_chunk), snapshot_blocks=3, snapshot_block_capacity=n * per_chunk)
     chans = list(range(n))
     dec.init_channels(chans)
     dev = [torch.from_numpy(r).cuda() for r in rows]
@@ -437,12 +450,13 @@ def test_snapshot_pipeline_over_calls_wraps_the_lattice_ring(torch_cuda, B):
             for od, r in zip(step, rows):
                 od.advance(r[k * chunk:(k + 1) * chunk])
             _check_paths(dec.best_path_batch(chans, use_final=False, snapshot=ids[k]), step, False, f"chunk {k}")
-            recs, offs = dec.lattice_arcs_batch(chans, snapshot=ids[k])
-            for ch in chans:
-                lo = 0 if k == 0 else k * chunk + 1
-                _assert_records(recs[offs[ch]:offs[ch + 1]], _oracle_lattice_of_frames(ods[ch], lo, (k + 1) * chunk + 1), f"chunk {k} ch {ch}")
+            lo = 0 if k == 0 else k * chunk + 1
+            _check_snapshot_lattice(dec, ids[k], chans, lambda ch: _oracle_lattice_of_frames(ods[ch], lo, (k + 1) * chunk + 1), f"chunk {k}")
     torch.cuda.synchronize()
     assert ids == sorted(set(ids))
+    with pytest.raises(B.WfstError) as e:                      # that block went to a later snapshot long ago
+        dec.snapshot_lattice_arcs(ids[nchunks - 4], chans)
+    assert e.value.code == B.WFST_E_NOT_INIT
     for ch in chans:
         assert dec.stats(ch)["status"] == 0 and dec.stats(ch)["lattice_arcs"] == len(ods[ch].lattice()[0])
         compare_channel(dec, ch, ods[ch], label=f"ring ch{ch}", lattice=False)
@@ -458,6 +472,9 @@ def test_snapshot_edge_cases(torch_cuda, B):
     og = oracle.OracleGraph(g)
     od = oracle.OracleDecoder(og, c.beam, c.lattice_beam, c.max_active)
     od.advance(rows)
+    half = oracle.OracleDecoder(og, c.beam, c.lattice_beam, c.max_active)
+    half.advance(rows[:20])
+    # --- without snapshot blocks: snapshots cover best paths, the arcs stay buffered
     dec = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=2, max_lanes=2, max_frames=40,
                         lattice_capacity=200_000)
     dec.init_channels([0, 1])
@@ -468,32 +485,44 @@ def test_snapshot_edge_cases(torch_cuda, B):
     first, count = dec.advance([0], [t[:20]], snapshot_every=20)
     assert count == 1
     dec.advance([0], [t[20:40]])
-    # channel 1 was not in the call: it has no such snapshot
-    r = dec.best_path_batch([0, 1], use_final=False, snapshot=first)
+    r = dec.best_path_batch([0, 1], use_final=False, snapshot=first)    # channel 1 was not in the call
     assert r[0]["status"] == 0 and r[1]["status"] == B.WFST_E_NOT_INIT
-    assert np.array_equal(r[0]["words"], (lambda o: (o.advance(rows[:20]), o.best_path(False)["words"])[1])(
-        oracle.OracleDecoder(og, c.beam, c.lattice_beam, c.max_active)))
-    recs, offs = dec.lattice_arcs_batch([1, 0], snapshot=first)
-    assert offs[1] == 0
-    _assert_records(recs, _oracle_lattice_of_frames(od, 0, 21), "snapshot drain")
-    # the live drain hands out the rest; a snapshot older than the drain point has nothing left
-    _assert_records(dec.lattice_arcs(0), _oracle_lattice_of_frames(od, 21, 41), "live drain after a snapshot drain")
-    recs, offs = dec.lattice_arcs_batch([0], snapshot=first)
-    assert offs[-1] == 0
-    # a call with zero frames still seals its snapshot (the state as it is)
-    first2, count2 = dec.advance([0], [t[:0]], snapshot_every=5)
+    assert np.array_equal(r[0]["words"], half.best_path(False)["words"])
+    with pytest.raises(B.WfstError) as e:
+        dec.snapshot_lattice_arcs(first, [0])
+    assert e.value.code == B.WFST_E_INVALID_ARG
+    _assert_records(dec.lattice_arcs(0), _oracle_lattice_of_frames(od, 0, 41), "live drain")
+    first2, count2 = dec.advance([0], [t[:0]], snapshot_every=5)        # zero frames: the state as it is
     assert count2 == 1 and first2 == first + 1
     r = dec.best_path_batch([0], use_final=True, snapshot=first2)[0]
     assert np.array_equal(r["words"], od.best_path(True)["words"])
-    # a ring too small for the arcs of one call stops the channel cleanly; the snapshot sealed before is intact
+    # --- with blocks: arcs buffered by plain calls go into the first snapshot sealed afterwards
+    decb = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=2, max_lanes=2, max_frames=40,
+                         lattice_capacity=200_000, snapshot_blocks=2, snapshot_block_capacity=200_000)
+    decb.init_channels([0, 1])
+    decb.advance([0], [t[:20]])
+    first, count = decb.advance([0], [t[20:40]], snapshot_every=10)
+    assert count == 2
+    _check_snapshot_lattice(decb, first, [1, 0], lambda ch: _oracle_lattice_of_frames(od, 0, 31 if ch == 0 else 0), "first block")
+    r = decb.snapshot_lattice_arcs(first + 1, [0], copy=False)
+    assert r["records"] is None and r["block"] and r["total"] == len(_oracle_lattice_of_frames(od, 31, 41)[0])
+    buf = torch.zeros(r["total"] * 12, dtype=torch.uint8, device="cuda")
+    r2 = decb.snapshot_lattice_arcs(first + 1, [0], out_device=buf)
+    got = np.frombuffer(buf.cpu().numpy().tobytes(), dtype=B.LAT_DTYPE)
+    _assert_records(got[r2["starts"][0]:r2["starts"][0] + r2["counts"][0]], _oracle_lattice_of_frames(od, 31, 41), "device copy")
+    with pytest.raises(B.WfstError) as e:       # more snapshots in one call than there are blocks
+        decb.advance([1], [t[:30]], snapshot_every=10)
+    assert e.value.code == B.WFST_E_INVALID_ARG
+    # a block too small for a lane's arcs stops the channel cleanly; earlier snapshots are intact
     need = len(_oracle_lattice_of_frames(od, 0, 21)[0])
     small = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=1, max_lanes=1, max_frames=40,
-                          lattice_capacity=int(need * 1.3))
+                          lattice_capacity=200_000, snapshot_blocks=2, snapshot_block_capacity=need)
     small.init_channels([0])
     first, count = small.advance([0], [t], snapshot_every=20)
     assert count == 2
     torch.cuda.synchronize()
+    want_second = len(_oracle_lattice_of_frames(od, 21, 41)[0])
+    assert want_second > need
     assert small.stats(0)["status"] == B.WFST_E_LATTICE_OVERFLOW
-    recs, offs = small.lattice_arcs_batch([0], snapshot=first)
-    _assert_records(recs, _oracle_lattice_of_frames(od, 0, 21), "snapshot of a channel that overflowed later")
     assert small.best_path_batch([0], snapshot=first + 1)[0]["status"] == B.WFST_E_LATTICE_OVERFLOW
+    _check_snapshot_lattice(small, first, [0], lambda ch: _oracle_lattice_of_frames(od, 0, 21), "block of an earlier snapshot")
