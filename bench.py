@@ -176,7 +176,8 @@ def main() -> int:
     if os.path.exists(tpath) and n_ch == cfg.n_streams:
         with open(tpath) as f:
             tj = json.load(f)
-        traffic = tj["fetch_bytes_per_launch"] + tj["write_bytes_per_launch"]
+        # measured per 50-frame chunk of all 500 lanes; a launch covers chunks_per_launch of them
+        traffic = round((tj["fetch_bytes_per_chunk"] + tj["write_bytes_per_chunk"]) * (K / max(launches, 1)))
 
     result = {
         "metric": "decode RTFx (audio s / wall s) + arcs expanded/s, batched streams, 1 GPU",

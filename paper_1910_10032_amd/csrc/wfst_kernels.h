@@ -707,13 +707,15 @@ __global__ void __launch_bounds__(NT, NT / 128) k_advance(DecDev D, const LanePa
         for (long long i0 = tid; i0 < n; i0 += (long long)NT * U) {
           LatInt r[U];
           uint32_t arc_id[U];
+          // loads are unconditional (a lane past the end re-reads the last record) so that all of a
+          // round's loads, and then all its gathers, are in flight together
 #pragma unroll
           for (int u = 0; u < U; ++u) {
-            const long long i = i0 + (long long)u * NT;
-            if (i < n) r[u] = lat[first + i < D.lat_cap ? first + i : first + i - D.lat_cap];
+            const long long i = min(i0 + (long long)u * NT, n - 1);
+            r[u] = lat[first + i < D.lat_cap ? first + i : first + i - D.lat_cap];
           }
 #pragma unroll
-          for (int u = 0; u < U; ++u) if (i0 + (long long)u * NT < n) arc_id[u] = D.g.orig[r[u].arc];
+          for (int u = 0; u < U; ++u) arc_id[u] = D.g.orig[r[u].arc];
 #pragma unroll
           for (int u = 0; u < U; ++u) {
             const long long i = i0 + (long long)u * NT;
@@ -762,6 +764,7 @@ __global__ void __launch_bounds__(NT, NT / 128) k_advance(DecDev D, const LanePa
     // snapshots still due in the state it is in
     if (n_sealed >= n_snaps) { if (more) continue; break; }
     seal();
+    PHASE_MARK(12);
   }
   __syncthreads();
   if (tid == 0) {
