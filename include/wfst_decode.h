@@ -98,6 +98,9 @@ typedef struct {
                                 cover best paths only                                       */
   int64_t snapshot_block_capacity; /* lattice arcs one block holds, all lanes of a call
                                 together; 0 = min(lattice_capacity, 4096 * max_lanes)     */
+  int32_t lane_threads;      /* threads of the workgroup that owns a lane: 512, 1024, or 0 =
+                                per call: 1024 if the call has no more lanes than the device
+                                has compute units, else 512.  Results do not depend on it.  */
 } wfst_config_t;
 
 typedef struct { int32_t frame; uint32_t arc; float extra_cost; } wfst_lat_arc_t;

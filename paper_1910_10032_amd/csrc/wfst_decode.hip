@@ -64,6 +64,7 @@ struct wfst_decoder {
   std::vector<int64_t> blk_ids;         // host mirror: snapshot id each block slot is assigned to
   long long *d_ranges = nullptr;        // readout scratch [2 * max(num_channels, max_lanes) + 1]
   bool profiling = false;
+  int num_cus = 0;                      // compute units of the device
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
 };
 
@@ -117,7 +118,15 @@ int launch_lanes(wfst_decoder *d, const std::vector<LaneParam> &lp, int is_init,
     HIP_TRY(hipEventCreate(&e0)); HIP_TRY(hipEventCreate(&e1));
     HIP_TRY(hipEventRecord(e0, stream));
   }
-  hipLaunchKernelGGL(k_advance<NT>, dim3(n), dim3(NT), 0, stream, d->dev, (const LaneParam *)d->d_params, is_init);
+  // A lane is one workgroup.  With at most one lane per compute unit a lane can have the whole
+  // unit: 1024 threads; with more lanes two 512-thread workgroups share a unit.  The results
+  // do not depend on the choice.
+  int threads = d->cfg.lane_threads;
+  if (threads == 0) threads = n <= d->num_cus ? 1024 : NT;
+  if (threads == 1024)
+    hipLaunchKernelGGL(k_advance<1024>, dim3(n), dim3(1024), 0, stream, d->dev, (const LaneParam *)d->d_params, is_init);
+  else
+    hipLaunchKernelGGL(k_advance<NT>, dim3(n), dim3(NT), 0, stream, d->dev, (const LaneParam *)d->d_params, is_init);
   HIP_TRY(hipGetLastError());
   if (e0) { HIP_TRY(hipEventRecord(e1, stream)); d->prof_events.push_back({e0, e1}); }
   return 0;
@@ -247,12 +256,20 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
   if (c.history_capacity == 0) c.history_capacity = ((int64_t)c.max_frames + 1) * c.max_active;
   if (c.lattice_capacity == 0) c.lattice_capacity = 64ll * c.max_active;
   if (c.snapshot_blocks < 0 || c.snapshot_block_capacity < 0) return WFST_E_INVALID_ARG;
+  if (c.lane_threads != 0 && c.lane_threads != 512 && c.lane_threads != 1024) return WFST_E_INVALID_ARG;
   if (!c.lattice_on) c.snapshot_blocks = 0;
   if (c.snapshot_blocks > 0 && c.snapshot_block_capacity == 0)
     c.snapshot_block_capacity = std::min<int64_t>(c.lattice_capacity, 4096ll * c.max_lanes);
   wfst_decoder *d = new (std::nothrow) wfst_decoder;
   if (!d) return WFST_E_DEVICE;
   d->graph = graph; d->cfg = c;
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+      (void)hipGetLastError(); delete d; return WFST_E_DEVICE;
+    }
+    d->num_cus = cus;
+  }
   DecDev &D = d->dev;
   D.g = graph->dev;
   int hbits = 4;

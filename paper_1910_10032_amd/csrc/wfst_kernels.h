@@ -632,7 +632,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
 
 // One workgroup per lane.  is_init: (re)start the lane's channel and write frame 0.
 template <int NT>
-__global__ void __launch_bounds__(NT, NT / 128) k_advance(DecDev D, const LaneParam *__restrict__ lanes, int is_init) {
+__global__ void __launch_bounds__(NT, 4) k_advance(DecDev D, const LaneParam *__restrict__ lanes, int is_init) {
   __shared__ LaneShared<NT> S;
   const int tid = threadIdx.x;
   const LaneParam lp = lanes[blockIdx.x];

@@ -71,27 +71,31 @@ def test_small_random_graphs(torch_cuda, B, seed):
         T = int(rng.integers(1, 40))
         rows.append((-rng.integers(0, 5, size=(T, 12)).astype(F32)) if integer else rng.normal(-4, 2, size=(T, 12)).astype(F32))
     rows.append(np.zeros((0, 12), F32))          # a stream that gets no frames
-    dec, ods, _ = run_pair(torch_cuda, B, g, rows, beam=7.0, lbeam=3.0, alpha=20)
+    # the lane workgroup size changes nothing: both sizes, alternating over the seeds
+    dec, ods, _ = run_pair(torch_cuda, B, g, rows, beam=7.0, lbeam=3.0, alpha=20, lane_threads=(512, 1024)[seed // 2 % 2])
     for ch, od in enumerate(ods):
         compare_channel(dec, ch, od, label=f"seed{seed}/ch{ch}")
 
 
-def test_max_active_ties(torch_cuda, B):
+@pytest.mark.parametrize("lane_threads", [512, 1024])
+def test_max_active_ties(torch_cuda, B, lane_threads):
     """Integer costs: the max-active cut falls inside large groups of equal cost."""
     rng = np.random.default_rng(77)
     g = random_graph(rng, num_states=400, n_emit_per_state=(3, 6), eps_prob=0.004, num_pdfs=6, wmax=2, integer=True, n_final=20)
     rows = [-rng.integers(0, 3, size=(30, 6)).astype(F32) for _ in range(3)]
-    dec, ods, _ = run_pair(torch_cuda, B, g, rows, beam=6.0, lbeam=2.0, alpha=37, token_capacity=2048)
+    dec, ods, _ = run_pair(torch_cuda, B, g, rows, beam=6.0, lbeam=2.0, alpha=37, token_capacity=2048, lane_threads=lane_threads)
     for ch, od in enumerate(ods):
         assert od.max_tokens_pre_prune > 37
         compare_channel(dec, ch, od, label=f"ties/ch{ch}")
 
 
-def test_config0_full(torch_cuda, B):
+@pytest.mark.parametrize("lane_threads", [512, 1024])
+def test_config0_full(torch_cuda, B, lane_threads):
     c = synth.configs()[0]
     g = synth.make_graph(c.graph)
     rows = [c.loglikes(0, 0, c.length(0))]
-    dec, ods, _ = run_pair(torch_cuda, B, g, rows, c.beam, c.lattice_beam, c.max_active, lattice_capacity=1 << 20)
+    dec, ods, _ = run_pair(torch_cuda, B, g, rows, c.beam, c.lattice_beam, c.max_active, lattice_capacity=1 << 20,
+                           lane_threads=lane_threads)
     compare_channel(dec, 0, ods[0], label="cfg0")
 
 
@@ -106,13 +110,14 @@ def test_config0_chunked_interleaved_lanes(torch_cuda, B):
         compare_channel(dec, ch, od, label=f"cfg0-chunk/ch{ch}")
 
 
-def test_config1_prefix(torch_cuda, B):
+@pytest.mark.parametrize("lane_threads", [512, 1024])
+def test_config1_prefix(torch_cuda, B, lane_threads):
     """Config 1 (200k states, max-active saturates): first 120 frames, every frame compared."""
     c = synth.configs()[1]
     g = synth.make_graph(c.graph)
     rows = [c.loglikes(0, 0, 120)]
     dec, ods, _ = run_pair(torch_cuda, B, g, rows, c.beam, c.lattice_beam, c.max_active, token_capacity=1 << 16,
-                           lattice_capacity=1 << 21)
+                           lattice_capacity=1 << 21, lane_threads=lane_threads)
     assert ods[0].max_tokens_pre_prune > c.max_active
     compare_channel(dec, 0, ods[0], label="cfg1")
 
@@ -199,6 +204,9 @@ def test_argument_errors(torch_cuda, B):
     rng = np.random.default_rng(6)
     g = random_graph(rng, num_states=10, n_emit_per_state=(1, 2), eps_prob=0.1, num_pdfs=3)
     gg = B.WfstGraph(g)
+    with pytest.raises(B.WfstError) as e:
+        B.WfstDecoder(gg, 5.0, 2.0, 10, num_channels=3, max_lanes=2, max_frames=4, lane_threads=256)
+    assert e.value.code == B.WFST_E_INVALID_ARG
     dec = B.WfstDecoder(gg, 5.0, 2.0, 10, num_channels=3, max_lanes=2, max_frames=4)
     t = torch_cuda.zeros((2, 3), dtype=torch_cuda.float32, device="cuda")
     for bad, code in (([5], B.WFST_E_BAD_CHANNEL), ([1], B.WFST_E_NOT_INIT)):
@@ -392,7 +400,7 @@ def test_snapshots_sealed_inside_one_call(torch_cuda, B):
         od.advance(r)
     gg = B.WfstGraph(g)
     dec = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=n, max_lanes=n, max_frames=T,
-                        lattice_capacity=40_000, snapshot_blocks=T // chunk, snapshot_block_capacity=60_000)
+                        lattice_capacity=40_000, snapshot_blocks=T // chunk, snapshot_block_capacity=60_000, lane_threads=512)
     chans = list(range(n))
     dec.init_channels(chans)
     dev = [torch.from_numpy(r).cuda() for r in rows]
