@@ -97,17 +97,24 @@ __device__ __forceinline__ int ht_find(const Slot *slots, uint32_t mask, int hbi
 
 // Small frames keep the state table in LDS; a frame that outgrows it is redone with the
 // lane's table in global memory (nothing is committed before the contraction stage).
-constexpr int LDS_SLOTS = 4096, LDS_HBITS = 12, LDS_CLAIM_LIMIT = 3072, LDS_NIN_MAX = 1024;
+// A 512-thread lane shares its compute unit's 160 KB of LDS with another lane, a 1024-thread
+// lane has it to itself and takes a table, queue and limits twice as large.
+template <int NT> struct LdsCfg {
+  static constexpr int SLOTS = NT >= 1024 ? 8192 : 4096;
+  static constexpr int HBITS = NT >= 1024 ? 13 : 12;
+  static constexpr int CLAIM_LIMIT = SLOTS * 3 / 4;   // states touched in a frame
+  static constexpr int NIN_MAX = SLOTS / 4;           // tokens the frame starts from
+  static constexpr int QCAP = SLOTS;                  // entries of the LDS token queue (16-bit each)
+};
 constexpr int EXP_U = 4;                   // arcs per thread and round of the emitting expansion
 constexpr int EPS_U = 2;                   // epsilon arcs of a token fetched together
 constexpr int LAT_U = 4;                   // candidate records per thread and round of the lattice stage
 constexpr uint32_t AUX_EPS = 0x80000000u;  // Aux::slot flag: the record is an epsilon arc
-constexpr int LDS_QCAP = 4096;             // entries of the LDS token queue (16-bit each)
 // Slot::aux while a frame is being built (afterwards: index of the kept token, or ~0):
 constexpr uint32_t A_FRESH = 0x80000000u;  // epsilon out-degree not counted yet
 constexpr uint32_t A_KEPT_MAX = 0x20000000u;  // aux < A_KEPT_MAX: index of the kept token
-// LDS queue entry: slot (12 bits) | LQ_EPS | LQ_DUP
-constexpr uint32_t LQ_EPS = 0x4000u, LQ_DUP = 0x8000u, LQ_SLOT = 0x0FFFu;
+// LDS queue entry: slot (up to 14 bits) | LQ_EPS | LQ_DUP
+constexpr uint32_t LQ_EPS = 0x4000u, LQ_DUP = 0x8000u, LQ_SLOT = 0x3FFFu;
 
 template <int NT>
 struct LaneShared {
@@ -127,8 +134,8 @@ struct LaneShared {
 #ifdef WFST_PHASE_TIMING
   unsigned long long ph[16], tlast, dbg_tok, dbg_iters, dbg_arcs;
 #endif
-  uint16_t lq[LDS_QCAP];       // token queue of small frames
-  Slot table[LDS_SLOTS];       // state table of small frames
+  uint16_t lq[LdsCfg<NT>::QCAP];     // token queue of small frames
+  Slot table[LdsCfg<NT>::SLOTS];     // state table of small frames
 };
 
 #ifdef WFST_PHASE_TIMING
@@ -239,8 +246,8 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
   const int tid = threadIdx.x;
   const uint32_t *rec = D.g.rec;
   Slot *slots = LDS ? S.table : gslots;
-  const uint32_t mask = LDS ? (uint32_t)(LDS_SLOTS - 1) : D.H - 1;
-  const int hbits = LDS ? LDS_HBITS : D.hbits;
+  const uint32_t mask = LDS ? (uint32_t)(LdsCfg<NT>::SLOTS - 1) : D.H - 1;
+  const int hbits = LDS ? LdsCfg<NT>::HBITS : D.hbits;
   const Slot fresh{~0ull, EMPTY, A_FRESH};
 
   if (tid == 0) {
@@ -254,7 +261,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
   if (nf > D.max_frames) abort_code = E_HISTORY_OVERFLOW;
 
   // the frame's token queue: claimed slots, plus re-expansion requests for improved ones
-  const uint32_t qcap = LDS ? (uint32_t)LDS_QCAP : (uint32_t)D.qcap;
+  const uint32_t qcap = LDS ? (uint32_t)LdsCfg<NT>::QCAP : (uint32_t)D.qcap;
   auto qget = [&](uint32_t i, uint32_t &sl, bool &eps, bool &dup) {
     if (LDS) { const uint32_t e = S.lq[i]; sl = e & LQ_SLOT; eps = e & LQ_EPS; dup = e & LQ_DUP; }
     else { const uint32_t e = queue[i]; sl = e & Q_SLOT; eps = e & Q_EPS; dup = e & Q_DUP; }
@@ -263,7 +270,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
     if (!dup) {
       const uint32_t ci = wave_alloc(&S.nclaim);
       if (ci >= (uint32_t)D.tokcap) atomicOr(&S.flags, F_TOKOVF);
-      else if (LDS && ci >= (uint32_t)LDS_CLAIM_LIMIT) atomicOr(&S.flags, F_RESTART);
+      else if (LDS && ci >= (uint32_t)LdsCfg<NT>::CLAIM_LIMIT) atomicOr(&S.flags, F_RESTART);
     }
     const uint32_t q = wave_alloc(&S.qtail);
     if (q >= qcap) atomicOr(&S.flags, LDS ? F_RESTART : F_TOKOVF);
@@ -451,7 +458,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
   if (LDS) {
     wg_sync<true>();
     if (abort_code == 0 && (S.flags & F_RESTART)) {     // outgrew the LDS table: wipe it, redo with the global one
-      for (int i = tid; i < LDS_SLOTS; i += NT) slots[i] = fresh;
+      for (int i = tid; i < LdsCfg<NT>::SLOTS; i += NT) slots[i] = fresh;
       __syncthreads();
       return false;
     }
@@ -596,7 +603,7 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
 
   // ---- 6. clear the table ---------------------------------------------------------------
   if (S.flags & F_TOKOVF) {                                        // untracked claims: wipe everything
-    const uint32_t n_all = LDS ? (uint32_t)LDS_SLOTS : D.H;
+    const uint32_t n_all = LDS ? (uint32_t)LdsCfg<NT>::SLOTS : D.H;
     for (uint32_t i = tid; i < n_all; i += NT) slots[i] = fresh;
   } else {
     for (uint32_t i = tid; i < n_q; i += NT) {
@@ -647,7 +654,7 @@ __global__ void __launch_bounds__(NT, 4) k_advance(DecDev D, const LaneParam *__
   LatInt *lat = D.lat + (size_t)lp.chan * (size_t)D.lat_cap;
 
   const Slot fresh{~0ull, EMPTY, A_FRESH};
-  for (int i = tid; i < LDS_SLOTS; i += NT) S.table[i] = fresh;
+  for (int i = tid; i < LdsCfg<NT>::SLOTS; i += NT) S.table[i] = fresh;
   if (tid == 0) {
     if (is_init) {
       S.status = 0; S.nf = 0; S.hist_used = 0; S.lat_room = D.lat_cap; S.lat_pos = 0; S.lat_total = 0; S.arcs_expanded = 0;
@@ -744,7 +751,7 @@ __global__ void __launch_bounds__(NT, 4) k_advance(DecDev D, const LaneParam *__
     if (more) {
       const float *ll = is_init ? nullptr : lp.ll + (size_t)f * (size_t)lp.stride;
       bool small = is_init != 0;
-      if (!small) small = S.n_in <= LDS_NIN_MAX;
+      if (!small) small = S.n_in <= LdsCfg<NT>::NIN_MAX;
       bool done = false;
       if (small) done = lane_frame<NT, true>(D, S, lp, ll, is_init != 0, slots, queue, aux, dkey, dslot, foff, hist, lat);
       if (!done) {
