@@ -54,6 +54,8 @@ def main() -> int:
                          "(default: the block is handed over in place, by address and per-channel ranges)")
     ap.add_argument("--chunks-per-call", type=int, default=0,
                     help="chunks one advance call covers (0: all chunks of the warm-up / of the timed region)")
+    ap.add_argument("--beam", type=float, default=0.0,
+                    help="decode with another beam than the config's 13 (a sweep point, not the benchmark: the JSON says so)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 1 GiB device copy (calibrates the HBM byte counters under rocprofv3)")
     args = ap.parse_args()
@@ -81,6 +83,7 @@ def main() -> int:
     torch.cuda.set_device(0)
     cfg = synth.configs()[3]
     n_ch = args.channels or cfg.n_streams
+    beam = args.beam or cfg.beam
     chunk = cfg.chunk
     K, W = args.steps, args.warmup
     n_frames = (K + W) * chunk
@@ -94,9 +97,13 @@ def main() -> int:
     for s in range(n_ch):
         synth.device_loglikes(scores[s], cfg.ll_seed, s, 0, cfg.ll_mu, cfg.ll_sigma, cfg.ll_boost)
     torch.cuda.synchronize()
-    dec = B.WfstDecoder(graph, cfg.beam, cfg.lattice_beam, cfg.max_active, num_channels=n_ch, max_lanes=n_ch,
-                        max_frames=n_frames, token_capacity=16384, history_capacity=2_500_000,
-                        lattice_capacity=400_000, snapshot_blocks=max(K, W, 1), snapshot_block_capacity=16_000 * n_ch)
+    # buffer sizes for the benchmark's beam; a wider beam of a sweep keeps many more tokens per frame
+    scale = 1 if beam <= cfg.beam else 8
+    dec = B.WfstDecoder(graph, beam, cfg.lattice_beam, cfg.max_active, num_channels=n_ch, max_lanes=n_ch,
+                        max_frames=n_frames, token_capacity=16384 * (4 if scale > 1 else 1),
+                        history_capacity=1250 * scale * n_frames, lattice_capacity=400_000 * scale,
+                        snapshot_blocks=max(K, W, 1),
+                        snapshot_block_capacity=16_000 * (scale if beam <= cfg.beam + 3 else 64) * n_ch)
     ch_np = np.arange(n_ch, dtype=np.int32)
     dec.init_channels(ch_np)
     stream = torch.cuda.Stream().cuda_stream
@@ -173,7 +180,7 @@ def main() -> int:
     # scaled by a plain copy of known size); not measurable from inside this process
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "k_advance_config3_traffic.json")
-    if os.path.exists(tpath) and n_ch == cfg.n_streams:
+    if os.path.exists(tpath) and n_ch == cfg.n_streams and beam == cfg.beam:
         with open(tpath) as f:
             tj = json.load(f)
         # measured per 50-frame chunk of all 500 lanes; a launch covers chunks_per_launch of them
@@ -186,7 +193,7 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "configs[3]: 8M-state/23M-arc synthetic graph, %d channels x %d-frame chunks, beam %g, "
                                "max-active %d, lattice-beam %g, per-chunk best-path + lattice readout%s"
-                               % (n_ch, chunk, cfg.beam, cfg.max_active, cfg.lattice_beam, ("" if overlap else " (lock-step)") if readout else " (readout off)"),
+                               % (n_ch, chunk, beam, cfg.max_active, cfg.lattice_beam, ("" if overlap else " (lock-step)") if readout else " (readout off)"),
                    "channels": n_ch, "chunk_frames": chunk, "stream_frames_timed": K * n_ch * chunk,
                    "chunks_per_advance_call": (args.chunks_per_call or K) if overlap else 1},
         "arcs_expanded_per_s": round(arcs / wall, 1),
@@ -212,7 +219,7 @@ def main() -> int:
         t_c = time.perf_counter()
         c_arcs, c_frames = 0, 0
         for s in range(ns):
-            od = oracle.OracleDecoder(og, cfg.beam, cfg.lattice_beam, cfg.max_active)
+            od = oracle.OracleDecoder(og, beam, cfg.lattice_beam, cfg.max_active)
             rows = cfg.loglikes(s, 0, n_frames)
             od.advance(rows)
             c_arcs += od.arcs_expanded

@@ -47,11 +47,14 @@ def decode_and_compare(cfg, sample, token_capacity, history_capacity, lattice_ca
         first, count = dec.advance_ptrs(chans, (base + starts[:-1] * P * 4).astype(np.uint64), strides,
                                         lens.astype(np.int32), stream, snapshot_every=chunk)
         assert count == (T + chunk - 1) // chunk
+        handed_over = np.zeros(n_ch, np.int64)
         for j in range(count):
             paths = dec.best_path_batch(chans, use_final=False, words_cap=1024, raw=True, snapshot=first + j)
             assert (paths[4] == 0).all()
             r = dec.snapshot_lattice_arcs(first + j, chans)
             assert r["counts"].sum() == r["total"]
+            handed_over += r["counts"]
+            last_paths = paths
             for s in sample:
                 lat[s].append(r["records"][r["starts"][s]:r["starts"][s] + r["counts"][s]])
                 partial[s].append(paths[0][s, :paths[1][s]].copy())
@@ -63,6 +66,14 @@ def decode_and_compare(cfg, sample, token_capacity, history_capacity, lattice_ca
             final_checks.append((s, dec.final_lattice(s, True), dec.final_lattice(s, False)))
             lat[s].append(dec.lattice_arcs(s))
     torch.cuda.synchronize()
+    if cfg.chunk:
+        # every channel, not only the sampled ones: all its lattice arcs were handed over through
+        # the snapshots, and the last snapshot's best path is the live one
+        assert np.array_equal(handed_over, np.array([dec.stats(int(c))["lattice_arcs"] for c in chans]))
+        live = dec.best_path_batch(chans, use_final=False, words_cap=1024, raw=True)
+        assert np.array_equal(live[1], last_paths[1]) and np.array_equal(live[2].view(np.uint32), last_paths[2].view(np.uint32))
+        for c in range(n_ch):
+            assert np.array_equal(live[0][c, :live[1][c]], last_paths[0][c, :last_paths[1][c]])
     statuses = [dec.stats(int(c))["status"] for c in chans]
     assert all(st == 0 for st in statuses), f"channels with errors: {[(i, s) for i, s in enumerate(statuses) if s][:5]}"
     og = oracle.OracleGraph(g)
