@@ -52,6 +52,8 @@ def main() -> int:
     ap.add_argument("--copy-lattice", action="store_true",
                     help="also copy each snapshot's lattice block from the decoder's memory into a buffer of the caller "
                          "(default: the block is handed over in place, by address and per-channel ranges)")
+    ap.add_argument("--lattice-to-host", action="store_true",
+                    help="copy each snapshot's lattice block to pinned host memory (the PCIe-inclusive variant; never the benchmark)")
     ap.add_argument("--chunks-per-call", type=int, default=0,
                     help="chunks one advance call covers (0: all chunks of the warm-up / of the timed region)")
     ap.add_argument("--beam", type=float, default=0.0,
@@ -110,6 +112,7 @@ def main() -> int:
     strides, nfr = np.full(n_ch, P, np.int32), np.full(n_ch, chunk, np.int32)
     row0 = scores.data_ptr() + np.arange(n_ch, dtype=np.uint64) * np.uint64(n_frames * P * 4)
     lat_buf = torch.empty(n_ch * 80_000 * 12, dtype=torch.uint8, device="cuda")
+    host_buf = torch.empty(lat_buf.numel(), dtype=torch.uint8, pin_memory=True) if args.lattice_to_host else None
     chans = list(range(n_ch))
     readout = not args.no_readout
     overlap = readout and not args.sync_readout
@@ -123,7 +126,8 @@ def main() -> int:
         memory in the caller's form: returns (paths, number of arcs)."""
         paths = dec.best_path_batch(ch_np, use_final=False, words_cap=1024, raw=True, snapshot=snapshot)
         if snapshot:
-            r = dec.snapshot_lattice_arcs(snapshot, ch_np, out_device=lat_buf, copy=args.copy_lattice)
+            r = dec.snapshot_lattice_arcs(snapshot, ch_np, out_device=None if host_buf is not None else lat_buf,
+                                          out_host=host_buf, copy=args.copy_lattice or host_buf is not None)
             return paths, int(r["total"])
         return paths, int(dec.lattice_arcs_batch(ch_np, out_device=lat_buf)[-1])
 
@@ -193,7 +197,7 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "configs[3]: 8M-state/23M-arc synthetic graph, %d channels x %d-frame chunks, beam %g, "
                                "max-active %d, lattice-beam %g, per-chunk best-path + lattice readout%s"
-                               % (n_ch, chunk, beam, cfg.max_active, cfg.lattice_beam, ("" if overlap else " (lock-step)") if readout else " (readout off)"),
+                               % (n_ch, chunk, beam, cfg.max_active, cfg.lattice_beam, (("" if overlap else " (lock-step)") + (" + lattice copied to host" if host_buf is not None else "")) if readout else " (readout off)"),
                    "channels": n_ch, "chunk_frames": chunk, "stream_frames_timed": K * n_ch * chunk,
                    "chunks_per_advance_call": (args.chunks_per_call or K) if overlap else 1},
         "arcs_expanded_per_s": round(arcs / wall, 1),

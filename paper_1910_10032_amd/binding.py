@@ -314,10 +314,12 @@ class WfstDecoder:
             _check(rc, "wfst_decode_lattice_arcs_batch")
             return out[:offs[-1]].copy(), offs
 
-    def snapshot_lattice_arcs(self, snapshot: int, channels, out_device=None, copy: bool = True, cap: int = 1 << 20):
+    def snapshot_lattice_arcs(self, snapshot: int, channels, out_device=None, copy: bool = True, cap: int = 1 << 20,
+                              out_host=None):
         """Lattice arcs of a sealed snapshot: dict(starts, counts, total, block) and, with copy,
         `records`: the snapshot's block on the host, or None when it went into the cuda tensor
-        `out_device`.  block = device address of the decoder's own block."""
+        `out_device` or into `out_host` (a CPU tensor, e.g. pinned, that the caller reuses).
+        block = device address of the decoder's own block."""
         ch = np.ascontiguousarray(channels, np.int32)
         n = len(ch)
         starts, counts = np.zeros(n, np.int64), np.zeros(n, np.int64)
@@ -327,6 +329,8 @@ class WfstDecoder:
             out, ptr, dev = None, None, 0
             if copy and out_device is not None:
                 cap, ptr, dev = out_device.numel() * out_device.element_size() // LAT_DTYPE.itemsize, out_device.data_ptr(), 1
+            elif copy and out_host is not None:
+                cap, ptr = out_host.numel() * out_host.element_size() // LAT_DTYPE.itemsize, out_host.data_ptr()
             elif copy:
                 out = np.zeros(max(cap, 1), LAT_DTYPE)
                 ptr = out.ctypes.data
