@@ -46,10 +46,12 @@ enum {
   WFST_E_INVALID_ARG = -1,      /* null pointer, negative size, value out of range            */
   WFST_E_BAD_GRAPH = -2,        /* malformed CSR (see wfst_decode_graph_load)                 */
   WFST_E_BAD_CHANNEL = -3,      /* channel id out of range or repeated within one call        */
-  WFST_E_NOT_INIT = -4,         /* channel used before wfst_decode_init_channels              */
+  WFST_E_NOT_INIT = -4,         /* channel used before wfst_decode_init_channels; a snapshot
+                                   that does not exist (any more)                             */
   WFST_E_CAPACITY = -5,         /* caller's buffer too small; the needed size is reported     */
   WFST_E_TOKEN_OVERFLOW = -6,   /* more candidate tokens in a frame than token_capacity       */
-  WFST_E_LATTICE_OVERFLOW = -7, /* lattice (or candidate) buffer of the channel is full       */
+  WFST_E_LATTICE_OVERFLOW = -7, /* lattice (or candidate) buffer of the channel, or the
+                                   snapshot's block, is full                                  */
   WFST_E_DEAD_CHANNEL = -8,     /* no token survived a frame                                  */
   WFST_E_NAN_INPUT = -9,        /* a score read by the channel was NaN or +inf                */
   WFST_E_BROKEN_TRACE = -10,    /* a best incoming arc starts at a state that holds no token  */

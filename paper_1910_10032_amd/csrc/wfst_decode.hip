@@ -142,7 +142,7 @@ const char *wfst_decode_strerror(int code) {
     case WFST_E_INVALID_ARG: return "invalid argument";
     case WFST_E_BAD_GRAPH: return "malformed graph";
     case WFST_E_BAD_CHANNEL: return "channel id out of range or repeated";
-    case WFST_E_NOT_INIT: return "channel not initialised";
+    case WFST_E_NOT_INIT: return "channel not initialised, or no such snapshot";
     case WFST_E_CAPACITY: return "caller buffer too small";
     case WFST_E_TOKEN_OVERFLOW: return "token capacity exceeded";
     case WFST_E_LATTICE_OVERFLOW: return "lattice capacity exceeded";
