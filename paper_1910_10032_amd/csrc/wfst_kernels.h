@@ -69,11 +69,9 @@ __device__ __forceinline__ int ht_insert(Slot *slots, uint32_t mask, int hbits, 
   uint32_t h = slot_hash(handle, hbits);
   claimed = false; improved = false;
   for (uint32_t probe = 0; probe <= mask; ++probe) {
-    uint32_t k = tl32<LDS>(&slots[h].handle);
-    if (k == EMPTY) {
-      k = atomicCAS(&slots[h].handle, EMPTY, handle);
-      if (k == EMPTY) { claimed = true; k = handle; }
-    }
+    // one compare-and-swap tells all three cases apart: free (now ours), ours already, another state's
+    uint32_t k = atomicCAS(&slots[h].handle, EMPTY, handle);
+    if (k == EMPTY) { claimed = true; k = handle; }
     if (k == handle) {
       unsigned long long old = atomicMin(&slots[h].val, K);
       improved = K < old;
@@ -123,7 +121,10 @@ struct LaneShared {
     struct { int scan[NT]; float cost[NT]; uint32_t base[NT]; };
     uint32_t hist[NBINS];
   };
-  uint32_t qtail, nclaim, auxn, best, flags, nvalid, nout, latn, kmin, kmax;
+  // queue entries (low word) and states claimed (high word) of the frame: one 64-bit counter,
+  // so that a claim takes one atomic for both
+  union { unsigned long long claim_ctr; struct { uint32_t qtail, nclaim; }; };
+  uint32_t auxn, best, flags, nvalid, nout, latn, kmin, kmax;
   uint32_t sel_bin, sel_below, sel_cnt;
   unsigned long long emit_arcs, eps_arcs;
   // channel state, cached for the duration of the call
@@ -267,12 +268,20 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
     else { const uint32_t e = queue[i]; sl = e & Q_SLOT; eps = e & Q_EPS; dup = e & Q_DUP; }
   };
   auto on_claim = [&](int sl, uint32_t dw, bool dup) {
+    // the lanes of the wave that call this together get consecutive queue entries and, those
+    // that claimed a new state, consecutive claim numbers, from a single 64-bit atomic add
+    const unsigned long long m_all = __ballot(1), m_new = __ballot(!dup);
+    const int wl = threadIdx.x & 63, leader = __ffsll((long long)m_all) - 1;
+    unsigned long long base = 0;
+    if (wl == leader) base = atomicAdd(&S.claim_ctr, ((unsigned long long)__popcll(m_new) << 32) | (unsigned long long)__popcll(m_all));
+    base = __shfl(base, leader, 64);
+    const unsigned long long below = (1ull << wl) - 1ull;
     if (!dup) {
-      const uint32_t ci = wave_alloc(&S.nclaim);
+      const uint32_t ci = (uint32_t)(base >> 32) + (uint32_t)__popcll(m_new & below);
       if (ci >= (uint32_t)D.tokcap) atomicOr(&S.flags, F_TOKOVF);
       else if (LDS && ci >= (uint32_t)LdsCfg<NT>::CLAIM_LIMIT) atomicOr(&S.flags, F_RESTART);
     }
-    const uint32_t q = wave_alloc(&S.qtail);
+    const uint32_t q = (uint32_t)base + (uint32_t)__popcll(m_all & below);
     if (q >= qcap) atomicOr(&S.flags, LDS ? F_RESTART : F_TOKOVF);
     else if (LDS) S.lq[q] = (uint16_t)((uint32_t)sl | ((dw & HAS_EPS) ? LQ_EPS : 0u) | (dup ? LQ_DUP : 0u));
     else queue[q] = (uint32_t)sl | ((dw & HAS_EPS) ? Q_EPS : 0u) | (dup ? Q_DUP : 0u);
