@@ -81,6 +81,19 @@ __device__ __forceinline__ int ht_insert(Slot *slots, uint32_t mask, int hbits, 
   }
   return -1;
 }
+// A whole slot at once: in LDS one 16-byte read instead of dependent 8- and 4-byte ones (a
+// reader beside concurrent atomic minima gets some value the slot held, which is all the
+// callers need); in global memory three independent coherent loads.
+template <bool LDS>
+__device__ __forceinline__ Slot ld_slot(const Slot *p) {
+  Slot r;
+  if (LDS) {
+    *reinterpret_cast<uint4 *>(&r) = *reinterpret_cast<const uint4 *>(p);
+  } else {
+    r.val = ld64(&p->val); r.handle = ld32(&p->handle); r.aux = ld32(&p->aux);
+  }
+  return r;
+}
 template <bool LDS>
 __device__ __forceinline__ int ht_find(const Slot *slots, uint32_t mask, int hbits, uint32_t handle) {
   uint32_t h = slot_hash(handle, hbits);
@@ -413,14 +426,16 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
       for (uint32_t i0 = w0; i0 < w1; i0 += NT) {
         const uint32_t i = i0 + tid;
         bool act = false; uint32_t src = 0; float c = 0.f;
+        uint32_t h = 0, ne = 0, np = 0; bool first = false;
         if (i < w1) {
           bool eps, dup;
           qget(i, src, eps, dup);
-          if (eps) { c = key2f((uint32_t)(tl64<LDS>(&slots[src].val) >> 32)); act = c <= cutoff; }
+          if (eps) {
+            const Slot sv = ld_slot<LDS>(&slots[src]);
+            c = key2f((uint32_t)(sv.val >> 32)); act = c <= cutoff; h = sv.handle;
+          }
         }
-        uint32_t h = 0, ne = 0, np = 0; bool first = false;
         if (act) {
-          h = tl32<LDS>(&slots[src].handle);
           ne = rec[3 * (size_t)h]; np = rec[3 * (size_t)h + 1];
           first = atomicAnd(&slots[src].aux, ~A_FRESH) & A_FRESH;   // first expansion while within the cutoff
         }
@@ -492,12 +507,13 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
         uint32_t sl, eps;
         if (!token_slot(i, sl, eps)) continue;
         Slot *sp = slots + sl;
-        const unsigned long long v = tl64<LDS>(&sp->val);
+        const Slot sv = ld_slot<LDS>(sp);
+        const unsigned long long v = sv.val;
         const float c = key2f((uint32_t)(v >> 32));
         if (!(c <= cutoff)) continue;
         const uint32_t pos = wave_alloc(&S.nout);
         if (pos >= room) continue;
-        hist[out_base + pos] = HTok{tl32<LDS>(&sp->handle) | (eps ? HAS_EPS : 0u), c, (uint32_t)v, NO_ARC};
+        hist[out_base + pos] = HTok{sv.handle | (eps ? HAS_EPS : 0u), c, (uint32_t)v, NO_ARC};
         sp->aux = pos;
       }
       wg_sync<LDS>();
@@ -576,10 +592,10 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
         if (a[u].slot == 0xFFFFFFFFu) continue;
         if (!(a[u].slot & AUX_EPS)) {
           // emitting candidate {slot of the destination, x, arc, index of the source token}
-          const Slot *sp = slots + a[u].slot;
-          const uint32_t pos = tl32<LDS>(&sp->aux);
+          const Slot sv = ld_slot<LDS>(slots + a[u].slot);
+          const uint32_t pos = sv.aux;
           if (pos >= A_KEPT_MAX) continue;
-          const unsigned long long v = tl64<LDS>(&sp->val);
+          const unsigned long long v = sv.val;
           if (pack(okey(a[u].x), a[u].arc) == v) hist[out_base + pos].prev = a[u].src;
           if (D.lattice_on && a[u].x <= cutoff_eff) {
             const float extra = a[u].x - key2f((uint32_t)(v >> 32));
@@ -587,17 +603,17 @@ __device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &
           }
         } else {
           // epsilon arc {slot of the source | AUX_EPS, weight, arc, handle of the destination}
-          const Slot *ss = slots + (a[u].slot & ~AUX_EPS);
-          const uint32_t spos = tl32<LDS>(&ss->aux);
+          const Slot ssv = ld_slot<LDS>(slots + (a[u].slot & ~AUX_EPS));
+          const uint32_t spos = ssv.aux;
           if (spos >= A_KEPT_MAX) continue;                        // the source token was not kept
-          const float x = key2f((uint32_t)(tl64<LDS>(&ss->val) >> 32)) + a[u].x;
+          const float x = key2f((uint32_t)(ssv.val >> 32)) + a[u].x;
           if (!(x <= cutoff_eff)) continue;
           const int sl = ht_find<LDS>(slots, mask, hbits, a[u].src);
           if (sl < 0) continue;
-          const Slot *sp = slots + sl;
-          const uint32_t pos = tl32<LDS>(&sp->aux);
+          const Slot sv = ld_slot<LDS>(slots + sl);
+          const uint32_t pos = sv.aux;
           if (pos >= A_KEPT_MAX) continue;
-          const unsigned long long v = tl64<LDS>(&sp->val);
+          const unsigned long long v = sv.val;
           if (pack(okey(x), a[u].arc) == v) hist[out_base + pos].prev = spos | PREV_SAME;
           if (D.lattice_on) {
             const float extra = x - key2f((uint32_t)(v >> 32));
