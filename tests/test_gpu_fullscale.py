@@ -135,10 +135,11 @@ def test_config3_online_500_channels():
                        lattice_capacity=400_000, snapshot_blocks=40, snapshot_block_capacity=16_000 * cfg.n_streams)
 
 
-def test_config2_offline_ragged_batch():
+@pytest.mark.parametrize("lane_threads", [0, 512])      # 0: the library's choice (1024 threads for 100 lanes)
+def test_config2_offline_ragged_batch(lane_threads):
     cfg = synth.configs()[2]
-    decode_and_compare(cfg, sample=[0, 41, 99], token_capacity=32768, history_capacity=4_000_000,
-                       lattice_capacity=6_000_000)
+    decode_and_compare(cfg, sample=[0, 41, 99] if lane_threads == 0 else [7, 58], token_capacity=32768,
+                       history_capacity=4_000_000, lattice_capacity=6_000_000, lane_threads=lane_threads)
 
 
 def test_config4_large_graph():
