@@ -218,9 +218,8 @@ __device__ void block_select(LaneShared<NT> &S, int n, uint32_t need, uint32_t l
   constexpr int PER = NBINS / NT;
   uint32_t less = 0;
   for (;;) {
-    unsigned long long range = (unsigned long long)hi - lo + 1;
-    int shift = 0;
-    while ((range >> shift) > (unsigned long long)NBINS) ++shift;
+    int shift = 0;                           // bins of 2^shift values: the last value, hi, must fall into bin NBINS - 1 at most
+    while ((((unsigned long long)hi - lo) >> shift) >= (unsigned long long)NBINS) ++shift;
     for (int b = tid; b < NBINS; b += NT) S.hist[b] = 0;
     __syncthreads();
     for (int i = tid; i < n; i += NT) {

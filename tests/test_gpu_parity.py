@@ -534,3 +534,21 @@ def test_snapshot_edge_cases(torch_cuda, B):
     assert small.stats(0)["status"] == B.WFST_E_LATTICE_OVERFLOW
     assert small.best_path_batch([0], snapshot=first + 1)[0]["status"] == B.WFST_E_LATTICE_OVERFLOW
     _check_snapshot_lattice(small, first, [0], lambda ch: _oracle_lattice_of_frames(od, 0, 21), "block of an earlier snapshot")
+
+
+def test_max_active_cut_at_a_histogram_bin_edge(torch_cuda, B):
+    """The exact selection bins the cost keys of a frame; here the largest key is exactly
+    1024 bins of 2^9 above the smallest (costs 62.0 .. 64.0), the edge at which the top key
+    must still fall into the last bin.  Three states share the cost at the cut."""
+    from helpers import graph_from_arcs
+    costs = [62.0, 63.0, 64.0, 64.0, 64.0, 66.0]
+    arcs = [(0, 1 + i, 1, 1 + i, w) for i, w in enumerate(costs)]
+    arcs += [(1 + i, 1 + i, 1, 0, 1.0) for i in range(len(costs))]           # self loops keep every state alive
+    g = graph_from_arcs(1 + len(costs), arcs, num_pdfs=1, finals={1: 0.0})
+    rows = [np.zeros((3, 1), F32)]
+    for lane_threads in (512, 1024):
+        dec, ods, _ = run_pair(torch_cuda, B, g, rows, beam=7.0, lbeam=7.0, alpha=3, lane_threads=lane_threads)
+        assert ods[0].max_tokens_pre_prune == 6 and ods[0].max_tokens == 3
+        s, c, _ = ods[0].tokens(1)
+        assert list(s) == [1, 2, 3] and list(c) == [62.0, 63.0, 64.0]          # the tie goes to the smallest state id
+        compare_channel(dec, 0, ods[0], label=f"bin-edge/{lane_threads}")
