@@ -28,7 +28,7 @@ def _same_records(got, want, label):
     assert np.array_equal(got["extra_cost"][o].view(np.uint32), ex.view(np.uint32)), label
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(48))
 def test_random_call_patterns(seed):
     import torch
 
@@ -44,6 +44,10 @@ def test_random_call_patterns(seed):
     lens = [int(rng.integers(5, 70)) for _ in range(n_ch)]
     rows = [(-rng.integers(0, 5, size=(T, num_pdfs)).astype(F32)) if integer else rng.normal(-4, 2, size=(T, num_pdfs)).astype(F32)
             for T in lens]
+    if seed % 5 == 3:                             # one stream dies: a frame whose scores are all -inf
+        rows[0][len(rows[0]) // 2, :] = -np.inf
+    if seed % 5 == 4:                             # one stream meets a NaN score
+        rows[-1][len(rows[-1]) // 3, :] = np.nan
     beam, lbeam = float(rng.choice([4.0, 7.0, 10.0])), float(rng.choice([0.0, 2.0, 5.0]))
     alpha = int(rng.choice([3, 12, 50, 5000]))
     og = oracle.OracleGraph(g)
@@ -108,3 +112,40 @@ def test_random_call_patterns(seed):
         if full[c].status == 0:
             _same_records(recs[offs[c]:offs[c + 1]], _records_of(full[c], handed[c], lens[c] + 1), f"seed {seed} rest ch {c}")
         compare_channel(dec, c, full[c], lattice=False, label=f"seed {seed} ch {c}")
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_heavy_frames(seed):
+    """Frames of thousands of tokens on the 200k-state synthetic graph with random beams,
+    max-active limits and score seeds: the max-active cut falls at many different places in
+    the cost range (every call of the exact selection bins a different key range), frames
+    start in the LDS table and outgrow it, or run on the global table from the start, with
+    both lane sizes and with chunked calls."""
+    import torch
+
+    import synth
+    from paper_1910_10032_amd import binding as B
+    assert torch.cuda.is_available()
+    rng = np.random.default_rng(9100 + seed)
+    c = synth.configs()[1]
+    g = synth.make_graph(c.graph)
+    beam = float(c.beam - rng.choice([0.0, 1.0, 2.0, 3.0]))
+    alpha = int(rng.choice([300, 1500, 4000, 7000]))
+    lbeam = float(rng.choice([1.0, 4.0]))
+    T = int(rng.integers(24, 40))
+    stream_id = int(rng.integers(0, 1000))
+    rows = synth.host_loglikes(c.ll_seed + seed, stream_id, 0, T, c.graph.num_pdfs, c.ll_mu, c.ll_sigma, c.ll_boost)
+    od = oracle.OracleDecoder(oracle.OracleGraph(g), beam, lbeam, alpha)
+    od.advance(rows)
+    dec = B.WfstDecoder(B.WfstGraph(g), beam, lbeam, alpha, num_channels=1, max_lanes=1, max_frames=T, token_capacity=1 << 16,
+                        lattice_capacity=len(od.lattice()[0]) + 16, lane_threads=int(rng.choice([512, 1024])))
+    dec.init_channels([0])
+    t = torch.from_numpy(rows).cuda()
+    pos = 0
+    while pos < T:
+        n = int(rng.integers(1, 9))
+        dec.advance([0], [t[pos:pos + n]])
+        pos += n
+    torch.cuda.synchronize()
+    assert od.max_tokens_pre_prune > 1500, "the case is meant to be heavy"
+    compare_channel(dec, 0, od, label=f"heavy seed {seed} beam {beam} alpha {alpha}")
