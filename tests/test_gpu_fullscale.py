@@ -146,3 +146,11 @@ def test_config4_large_graph():
     cfg = synth.configs()[4]
     decode_and_compare(cfg, sample=[3, 150], token_capacity=60000, history_capacity=12_000_000,
                        lattice_capacity=14_000_000, frame_step=3)
+
+
+def test_config1_whole_stream_with_max_active_binding():
+    """Config 1: one stream of 1000 frames on the 200k-state graph, ~26k tokens before and 7000
+    after pruning in nearly every frame, so the exact max-active selection runs a thousand
+    times at different places of the cost range; every frame is compared."""
+    cfg = synth.configs()[1]
+    decode_and_compare(cfg, sample=[0], token_capacity=1 << 16, history_capacity=8_000_000, lattice_capacity=8_000_000)

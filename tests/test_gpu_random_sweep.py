@@ -44,6 +44,8 @@ def test_random_call_patterns(seed):
     lens = [int(rng.integers(5, 70)) for _ in range(n_ch)]
     rows = [(-rng.integers(0, 5, size=(T, num_pdfs)).astype(F32)) if integer else rng.normal(-4, 2, size=(T, num_pdfs)).astype(F32)
             for T in lens]
+    if seed % 7 == 5:                             # positive log-likelihoods: path costs go negative
+        rows = [r + F32(7.0) for r in rows]
     if seed % 5 == 3:                             # one stream dies: a frame whose scores are all -inf
         rows[0][len(rows[0]) // 2, :] = -np.inf
     if seed % 5 == 4:                             # one stream meets a NaN score
