@@ -552,3 +552,43 @@ def test_max_active_cut_at_a_histogram_bin_edge(torch_cuda, B):
         s, c, _ = ods[0].tokens(1)
         assert list(s) == [1, 2, 3] and list(c) == [62.0, 63.0, 64.0]          # the tie goes to the smallest state id
         compare_channel(dec, 0, ods[0], label=f"bin-edge/{lane_threads}")
+
+
+@pytest.mark.parametrize("lane_threads,sizes", [(512, (1023, 1024, 1025, 3071, 3072, 3073, 4095, 4096, 4097)),
+                                                (1024, (2047, 2048, 2049, 6143, 6144, 6145, 8191, 8192, 8193))])
+def test_frames_at_the_limits_of_the_lds_table(torch_cuda, B, lane_threads, sizes):
+    """A fan of K states reached in frame 1 and kept alive by self loops: K sits just below, at
+    and just above the sizes at which a lane leaves its LDS table (tokens a frame starts from,
+    states it touches, table and queue sizes), for both lane sizes.  Same results either way."""
+    from helpers import graph_from_arcs
+    rng = np.random.default_rng(11)
+    for K in sizes:
+        w = rng.integers(0, 4, size=K).astype(float)
+        arcs = [(0, 1 + i, 1 + (i % 3), 1 + (i % 5), float(w[i])) for i in range(K)]
+        arcs += [(1 + i, 1 + i, 1 + ((i + 1) % 3), 0, 1.0) for i in range(K)]
+        arcs += [(1 + i, K + 1, 0, 2, 0.5) for i in range(0, K, 7)]            # some epsilon arcs into a common state
+        arcs += [(K + 1, K + 1, 1, 0, 0.25)]
+        g = graph_from_arcs(K + 2, arcs, num_pdfs=3, finals={K + 1: 0.0, 1: 1.0})
+        rows = [-rng.integers(0, 2, size=(4, 3)).astype(F32)]
+        dec, ods, _ = run_pair(torch_cuda, B, g, rows, beam=30.0, lbeam=2.0, alpha=20000, token_capacity=1 << 15,
+                               lattice_capacity=1 << 18, lane_threads=lane_threads)
+        assert ods[0].max_tokens >= K
+        compare_channel(dec, 0, ods[0], label=f"fan K={K} threads={lane_threads}")
+
+
+def test_history_and_lattice_buffers_filled_exactly(torch_cuda, B):
+    """Capacities that fit the run to the last token / record decode correctly; one less stops
+    the channel with the matching error."""
+    c = synth.configs()[0]
+    g = synth.make_graph(c.graph)
+    rows = [c.loglikes(0, 0, 30)]
+    od = oracle.OracleDecoder(oracle.OracleGraph(g), c.beam, c.lattice_beam, c.max_active)
+    od.advance(rows[0])
+    n_tok = sum(len(od.tokens(f)[0]) for f in range(od.num_frames))
+    n_lat = len(od.lattice()[0])
+    dec, ods, _ = run_pair(torch_cuda, B, g, rows, c.beam, c.lattice_beam, c.max_active, history_capacity=n_tok, lattice_capacity=n_lat)
+    compare_channel(dec, 0, ods[0], label="exact fit")
+    dec, _, _ = run_pair(torch_cuda, B, g, rows, c.beam, c.lattice_beam, c.max_active, history_capacity=n_tok - 1, lattice_capacity=n_lat)
+    assert dec.stats(0)["status"] == B.WFST_E_HISTORY_OVERFLOW
+    dec, _, _ = run_pair(torch_cuda, B, g, rows, c.beam, c.lattice_beam, c.max_active, history_capacity=n_tok, lattice_capacity=n_lat - 1)
+    assert dec.stats(0)["status"] == B.WFST_E_LATTICE_OVERFLOW
