@@ -592,3 +592,36 @@ def test_history_and_lattice_buffers_filled_exactly(torch_cuda, B):
     assert dec.stats(0)["status"] == B.WFST_E_HISTORY_OVERFLOW
     dec, _, _ = run_pair(torch_cuda, B, g, rows, c.beam, c.lattice_beam, c.max_active, history_capacity=n_tok, lattice_capacity=n_lat - 1)
     assert dec.stats(0)["status"] == B.WFST_E_LATTICE_OVERFLOW
+
+
+def test_final_lattice_over_a_wrapped_ring(torch_cuda, B):
+    """The lattice ring is a little larger than what the second part of the stream produces: the
+    first part is drained, the second part wraps around the end of the ring, and the final
+    lattice of what is buffered must be the checker's final lattice restricted to those frames
+    (the backward pass only ever looks at later frames)."""
+    c = synth.configs()[0]
+    g = synth.make_graph(c.graph)
+    T, cut = 60, 25
+    rows = c.loglikes(0, 0, T)
+    od = oracle.OracleDecoder(oracle.OracleGraph(g), c.beam, c.lattice_beam, c.max_active)
+    od.advance(rows)
+    fr = od.lattice()[0]
+    first_part, second_part = int((fr <= cut).sum()), int((fr > cut).sum())
+    cap = max(first_part, second_part) + 64
+    assert first_part + second_part > cap                     # the second part has to wrap
+    dec = B.WfstDecoder(B.WfstGraph(g), c.beam, c.lattice_beam, c.max_active, num_channels=1, max_lanes=1, max_frames=T,
+                        lattice_capacity=cap)
+    dec.init_channels([0])
+    t = torch_cuda.from_numpy(rows).cuda()
+    dec.advance([0], [t[:cut]])
+    _assert_records(dec.lattice_arcs(0), _oracle_lattice_of_frames(od, 0, cut + 1), "first part")
+    dec.advance([0], [t[cut:]])
+    for use_final in (True, False):
+        got, info = dec.final_lattice(0, use_final)
+        want = od.final_lattice(use_final)
+        m = want["frame"] > cut
+        o = np.lexsort((got["arc"], got["frame"]))
+        assert len(got) == int(m.sum()) and info["arcs_in"] == second_part
+        assert np.array_equal(got["frame"][o], want["frame"][m]) and np.array_equal(got["arc"][o], want["arc"][m])
+        assert np.array_equal(got["extra_cost"][o].view(np.uint32), want["extra"][m].view(np.uint32))
+    _assert_records(dec.lattice_arcs(0), _oracle_lattice_of_frames(od, cut + 1, T + 1), "second part, wrapped")
