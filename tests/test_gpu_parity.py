@@ -625,3 +625,36 @@ def test_final_lattice_over_a_wrapped_ring(torch_cuda, B):
         assert np.array_equal(got["frame"][o], want["frame"][m]) and np.array_equal(got["arc"][o], want["arc"][m])
         assert np.array_equal(got["extra_cost"][o].view(np.uint32), want["extra"][m].view(np.uint32))
     _assert_records(dec.lattice_arcs(0), _oracle_lattice_of_frames(od, cut + 1, T + 1), "second part, wrapped")
+
+
+def test_paths_with_many_words_per_frame(torch_cuda, B):
+    """Eight output labels per frame (one emitting arc and a chain of seven epsilon arcs, all
+    labelled): more than the remembered-path scratch of the batched best path holds (four words
+    per frame), so it must fall back to the full trace - live and on a snapshot - and a
+    too small words buffer must be reported with the size needed."""
+    from helpers import graph_from_arcs
+    n = 8
+    arcs = [(0, 1, 1, 1, 0.0)]
+    arcs += [(i, i + 1, 0, 1 + i, 0.0) for i in range(1, n)]
+    arcs += [(n, 1, 1, 9, 0.0)]
+    g = graph_from_arcs(n + 1, arcs, num_pdfs=1, finals={n: 0.0})
+    T = 40
+    rows = np.zeros((T, 1), F32)
+    od = oracle.OracleDecoder(oracle.OracleGraph(g), 5.0, 2.0, 100)
+    od.advance(rows)
+    want = od.best_path(True)
+    assert len(want["words"]) == 8 * T                               # 320 words > 4 * (T + 1) + 64
+    dec = B.WfstDecoder(B.WfstGraph(g), 5.0, 2.0, 100, num_channels=1, max_lanes=1, max_frames=T)
+    dec.init_channels([0])
+    first, count = dec.advance([0], [torch_cuda.from_numpy(rows).cuda()], snapshot_every=20)
+    half = oracle.OracleDecoder(oracle.OracleGraph(g), 5.0, 2.0, 100)
+    half.advance(rows[:20])
+    r = dec.best_path_batch([0], use_final=True, snapshot=first)[0]
+    assert r["status"] == 0 and np.array_equal(r["words"], half.best_path(True)["words"])
+    r = dec.best_path_batch([0], use_final=True, snapshot=first + 1)[0]
+    assert r["status"] == 0 and np.array_equal(r["words"], want["words"])
+    r = dec.best_path_batch([0], use_final=True)[0]
+    assert r["status"] == 0 and np.array_equal(r["words"], want["words"])
+    words, nw, tc, rf, st = dec.best_path_batch([0], use_final=True, words_cap=100, raw=True)
+    assert st[0] == B.WFST_E_CAPACITY and nw[0] == 8 * T              # the needed size comes back
+    assert np.array_equal(dec.best_path_arcs(0, True)["arcs"].astype(np.int64), want["arcs"])
