@@ -658,3 +658,37 @@ def test_paths_with_many_words_per_frame(torch_cuda, B):
     words, nw, tc, rf, st = dec.best_path_batch([0], use_final=True, words_cap=100, raw=True)
     assert st[0] == B.WFST_E_CAPACITY and nw[0] == 8 * T              # the needed size comes back
     assert np.array_equal(dec.best_path_arcs(0, True)["arcs"].astype(np.int64), want["arcs"])
+
+
+def test_two_decoders_share_a_graph_on_two_streams(torch_cuda, B):
+    """Two decoders on one graph, each fed on a stream of its own, calls interleaved without
+    waiting in between; a single-channel drain into device memory."""
+    torch = torch_cuda
+    c = synth.configs()[0]
+    g = synth.make_graph(c.graph)
+    gg = B.WfstGraph(g)
+    T, chunk = 60, 12
+    rows = [c.loglikes(s, 0, T) for s in range(6)]
+    og = oracle.OracleGraph(g)
+    ods = []
+    for r in rows:
+        od = oracle.OracleDecoder(og, c.beam, c.lattice_beam, c.max_active)
+        od.advance(r)
+        ods.append(od)
+    decs = [B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=3, max_lanes=3, max_frames=T,
+                          lattice_capacity=1 << 20) for _ in range(2)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    dev = [torch.from_numpy(r).cuda() for r in rows]
+    for d in decs:
+        d.init_channels([0, 1, 2])
+    for f0 in range(0, T, chunk):
+        for k, d in enumerate(decs):
+            d.advance([0, 1, 2], [dev[3 * k + i][f0:f0 + chunk] for i in range(3)], stream=streams[k].cuda_stream)
+    torch.cuda.synchronize()
+    buf = torch.zeros(len(ods[4].lattice()[0]) * 12, dtype=torch.uint8, device="cuda")
+    n = decs[1].lattice_arcs(1, out_device=buf)
+    got = np.frombuffer(buf.cpu().numpy().tobytes(), dtype=B.LAT_DTYPE)[:n]
+    _assert_records(got, _oracle_lattice_of_frames(ods[4], 0, T + 1), "drain into device memory")
+    for k, d in enumerate(decs):
+        for i in range(3):
+            compare_channel(d, i, ods[3 * k + i], label=f"decoder {k} ch {i}", lattice=not (k == 1 and i == 1))
