@@ -54,6 +54,7 @@ def main() -> int:
                          "(default: the block is handed over in place, by address and per-channel ranges)")
     ap.add_argument("--lattice-to-host", action="store_true",
                     help="copy each snapshot's lattice block to pinned host memory (the PCIe-inclusive variant; never the benchmark)")
+    ap.add_argument("--no-lock-step", action="store_true", help="skip the extra lock-step run reported for comparison")
     ap.add_argument("--chunks-per-call", type=int, default=0,
                     help="chunks one advance call covers (0: all chunks of the warm-up / of the timed region)")
     ap.add_argument("--beam", type=float, default=0.0,
@@ -134,7 +135,7 @@ def main() -> int:
     def all_stats():
         return [dec.stats(int(c)) for c in ch_np]
 
-    def run(first: int, count: int):
+    def run(first: int, count: int, overlap: bool = overlap):
         """Steps (chunks) [first, first + count), each decoded and read out."""
         last = None
         if not overlap:
@@ -215,6 +216,16 @@ def main() -> int:
     }
     if readout:
         result["lattice_arcs_last_chunk"] = int(last[1])
+    if overlap and not args.no_lock_step:
+        # the same chunks again, lock-step: one call per chunk, read out before the next is queued
+        dec.init_channels(ch_np)
+        run(0, W, overlap=False)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        run(W, K, overlap=False)
+        t3 = time.perf_counter()
+        result["lock_step"] = {"value": round(audio_s / (t3 - t2), 1), "ms_per_step": round((t3 - t2) / K * 1e3, 3),
+                               "note": "one advance call per chunk, its readouts before the next call"}
 
     if not args.no_cpu_baseline:
         import oracle
