@@ -25,6 +25,10 @@
 //      within the effective cutoff and the lattice beam is recorded with its extra cost;
 //      the arc equal to the table's minimum fixes the token's back-pointer;
 //   6. the touched table slots are cleared.
+// A call may cover many chunks of frames: at the boundaries the caller names, the lane seals
+// a snapshot of its channel (and hands its lattice records over in the caller's form) and
+// goes on, so that partial results can be read beside the decoding and no lane waits for a
+// slower one (the role of the paper's second stream, Section 3, Fig. 1).
 #pragma once
 #include "wfst_device.h"
 
