@@ -257,7 +257,7 @@ __device__ void block_select(LaneShared<NT> &S, int n, uint32_t need, uint32_t l
 // the lane's global table.  Returns false (LDS mode only) if the frame outgrew the LDS table
 // and must be redone with the global one; nothing has been committed in that case.
 template <int NT, bool LDS>
-__device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const LaneParam &lp, const float *ll, bool is_init,
+__device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const float *ll, bool is_init,
                            Slot *gslots, uint32_t *queue, Aux *aux, uint32_t *dkey, uint32_t *dslot,
                            long long *foff, HTok *hist, LatInt *lat) {
   const int tid = threadIdx.x;
@@ -781,12 +781,12 @@ __global__ void __launch_bounds__(NT, 4) k_advance(DecDev D, const LaneParam *__
       bool small = is_init != 0;
       if (!small) small = S.n_in <= LdsCfg<NT>::NIN_MAX;
       bool done = false;
-      if (small) done = lane_frame<NT, true>(D, S, lp, ll, is_init != 0, slots, queue, aux, dkey, dslot, foff, hist, lat);
+      if (small) done = lane_frame<NT, true>(D, S, ll, is_init != 0, slots, queue, aux, dkey, dslot, foff, hist, lat);
       if (!done) {
 #ifdef WFST_PHASE_TIMING
         if (tid == 0 && small) S.ph[6] += 1;
 #endif
-        lane_frame<NT, false>(D, S, lp, ll, is_init != 0, slots, queue, aux, dkey, dslot, foff, hist, lat);
+        lane_frame<NT, false>(D, S, ll, is_init != 0, slots, queue, aux, dkey, dslot, foff, hist, lat);
       }
 #ifdef WFST_PHASE_TIMING
       if (tid == 0) S.ph[5] += 1;
