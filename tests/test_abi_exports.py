@@ -40,6 +40,10 @@ def test_strerror_and_null_arguments(B):
     assert L.wfst_decode_create(None, None, None) == B.WFST_E_INVALID_ARG
     assert L.wfst_decode_advance(None, None, 0, None, None, None, None) == B.WFST_E_INVALID_ARG
     assert L.wfst_decode_graph_bytes(None, None, None) == B.WFST_E_INVALID_ARG
+    assert L.wfst_decode_advance_snapshots(None, None, 0, None, None, None, 10, None, None, None) == B.WFST_E_INVALID_ARG
+    assert L.wfst_decode_snapshot_wait(None, 1) == B.WFST_E_INVALID_ARG
+    assert L.wfst_decode_snapshot_best_path_batch(None, 1, None, 0, 0, None, 0, None, None, None, None) == B.WFST_E_INVALID_ARG
+    assert L.wfst_decode_snapshot_lattice_arcs(None, 1, None, 0, None, None, None, 0, 0, None, None) == B.WFST_E_INVALID_ARG
 
 
 def test_malformed_graphs_are_rejected_before_any_device_work(B):
