@@ -103,6 +103,9 @@ typedef struct {
   int32_t lane_threads;      /* threads of the workgroup that owns a lane: 512, 1024, or 0 =
                                 per call: 1024 if the call has no more lanes than the device
                                 has compute units, else 512.  Results do not depend on it.  */
+  int32_t frame_form;        /* 0 = per frame: the LDS-resident form for frames that fit it
+                                (when pdf ids fit in 16 bits), else the general form;
+                                1 = always the general form.  Results do not depend on it.  */
 } wfst_config_t;
 
 typedef struct { int32_t frame; uint32_t arc; float extra_cost; } wfst_lat_arc_t;

@@ -5,8 +5,9 @@ import subprocess
 _DIR = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(_DIR, "_libwfst_decode.so")
 SOURCES = [os.path.join(_DIR, "csrc", "wfst_decode.hip")]
-HEADERS = [os.path.join(_DIR, "csrc", "wfst_device.h"), os.path.join(_DIR, "csrc", "wfst_kernels.h"),
-           os.path.join(os.path.dirname(_DIR), "include", "wfst_decode.h")]
+HEADERS = [os.path.join(_DIR, "csrc", h) for h in ("wfst_device.h", "wfst_lane.h", "wfst_frame_general.h",
+                                                    "wfst_frame_light.h", "wfst_kernels.h")] + [
+    os.path.join(os.path.dirname(_DIR), "include", "wfst_decode.h")]
 
 
 def build(force: bool = True, verbose: bool = False) -> str:

@@ -125,6 +125,8 @@ int launch_lanes(wfst_decoder *d, const std::vector<LaneParam> &lp, int is_init,
   if (threads == 0) threads = n <= d->num_cus ? 1024 : NT;
   if (threads == 1024)
     hipLaunchKernelGGL(k_advance<1024>, dim3(n), dim3(1024), 0, stream, d->dev, (const LaneParam *)d->d_params, is_init);
+  else if (threads == 256)
+    hipLaunchKernelGGL(k_advance<256>, dim3(n), dim3(256), 0, stream, d->dev, (const LaneParam *)d->d_params, is_init);
   else
     hipLaunchKernelGGL(k_advance<NT>, dim3(n), dim3(NT), 0, stream, d->dev, (const LaneParam *)d->d_params, is_init);
   HIP_TRY(hipGetLastError());
@@ -183,14 +185,17 @@ int wfst_decode_graph_load(const wfst_csr_t *csr, wfst_graph_t **out) {
     rec.resize(3 * R); orig.assign(R, NO_ARC); label.resize(R); has_eps.assign(Q, 0);
   } catch (const std::bad_alloc &) { return WFST_E_DEVICE; }
   auto handle_of = [&](int32_t s) { return (uint32_t)((int64_t)s + csr->row_offsets[s]); };
-  for (int32_t s = 0; s < Q; ++s)
-    for (int64_t a = csr->row_offsets[s]; a < csr->row_offsets[s + 1]; ++a)
-      if (csr->ilabel[a] == 0) { has_eps[s] = 1; break; }
+  std::vector<uint32_t> n_emit, n_eps;
+  try { n_emit.assign(Q, 0); n_eps.assign(Q, 0); } catch (const std::bad_alloc &) { return WFST_E_DEVICE; }
+  for (int32_t s = 0; s < Q; ++s) {
+    for (int64_t a = csr->row_offsets[s]; a < csr->row_offsets[s + 1]; ++a) (csr->ilabel[a] ? n_emit[s] : n_eps[s])++;
+    has_eps[s] = n_eps[s] != 0;
+  }
+  const bool packed = csr->num_pdfs <= 65536;      // pdf ids leave the upper half of the third word free
   auto f2u = [](float x) { uint32_t u; std::memcpy(&u, &x, 4); return u; };
   for (int32_t s = 0; s < Q; ++s) {
     const uint32_t h = handle_of(s);
-    uint32_t ne = 0, np = 0;
-    for (int64_t a = csr->row_offsets[s]; a < csr->row_offsets[s + 1]; ++a) (csr->ilabel[a] ? ne : np)++;
+    const uint32_t ne = n_emit[s], np = n_eps[s];
     rec[3 * (size_t)h] = ne; rec[3 * (size_t)h + 1] = np; rec[3 * (size_t)h + 2] = f2u(csr->final_cost[s]);
     label[h] = s;
     uint32_t re = h + 1, rp = h + 1 + ne;            // next emitting / epsilon record
@@ -199,7 +204,9 @@ int wfst_decode_graph_load(const wfst_csr_t *csr, wfst_graph_t **out) {
       const uint32_t r = csr->ilabel[a] ? re++ : rp++;
       rec[3 * (size_t)r] = handle_of(d) | (has_eps[d] ? HAS_EPS : 0u);
       rec[3 * (size_t)r + 1] = f2u(csr->weight[a]);
-      rec[3 * (size_t)r + 2] = csr->ilabel[a] ? (uint32_t)(csr->ilabel[a] - 1) : (uint32_t)csr->olabel[a];
+      // third word: pdf id of an emitting arc, and above it the out-degrees of the destination
+      const uint32_t info = packed ? (degree_info(n_emit[d], n_eps[d]) << 16) : 0u;
+      rec[3 * (size_t)r + 2] = (csr->ilabel[a] ? (uint32_t)(csr->ilabel[a] - 1) : 0u) | info;
       label[r] = csr->olabel[a];
       orig[r] = (uint32_t)a;
     }
@@ -224,6 +231,8 @@ int wfst_decode_graph_load(const wfst_csr_t *csr, wfst_graph_t **out) {
   }
   g->dev.rec = d_rec; g->dev.orig = d_orig; g->dev.label = d_label;
   g->dev.num_records = (uint32_t)R; g->dev.start_handle = handle_of(csr->start_state); g->dev.num_pdfs = csr->num_pdfs;
+  g->dev.pdf_mask = packed ? 0xFFFFu : 0xFFFFFFFFu; g->dev.info_shift = packed ? 16 : 0;
+  g->dev.start_info = degree_info(n_emit[csr->start_state], n_eps[csr->start_state]);
   g->num_states = Q; g->num_arcs = E;
   g->decode_bytes = (int64_t)(12 * R); g->readout_bytes = (int64_t)(8 * R);
   *out = g;
@@ -256,7 +265,8 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
   if (c.history_capacity == 0) c.history_capacity = ((int64_t)c.max_frames + 1) * c.max_active;
   if (c.lattice_capacity == 0) c.lattice_capacity = 64ll * c.max_active;
   if (c.snapshot_blocks < 0 || c.snapshot_block_capacity < 0) return WFST_E_INVALID_ARG;
-  if (c.lane_threads != 0 && c.lane_threads != 512 && c.lane_threads != 1024) return WFST_E_INVALID_ARG;
+  if (c.lane_threads != 0 && c.lane_threads != 256 && c.lane_threads != 512 && c.lane_threads != 1024) return WFST_E_INVALID_ARG;
+  if (c.frame_form != 0 && c.frame_form != 1) return WFST_E_INVALID_ARG;
   if (!c.lattice_on) c.snapshot_blocks = 0;
   if (c.snapshot_blocks > 0 && c.snapshot_block_capacity == 0)
     c.snapshot_block_capacity = std::min<int64_t>(c.lattice_capacity, 4096ll * c.max_lanes);
@@ -278,6 +288,7 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
   D.qcap = (int32_t)std::min<int64_t>(2ll * c.token_capacity, 0x3FFFFFFF);
   D.auxcap = c.aux_capacity; D.tokcap = c.token_capacity; D.max_frames = c.max_frames; D.max_active = c.max_active;
   D.lattice_on = c.lattice_on ? 1 : 0; D.beam = c.beam; D.lattice_beam = c.lattice_beam;
+  D.force_general = c.frame_form == 1 ? 1 : 0;
   D.hist_cap = c.history_capacity; D.lat_cap = c.lattice_on ? c.lattice_capacity : 1;
   const size_t nc = (size_t)c.num_channels, nl = (size_t)c.max_lanes;
   int rc = 0;

@@ -30,644 +30,16 @@
 // goes on, so that partial results can be read beside the decoding and no lane waits for a
 // slower one (the role of the paper's second stream, Section 3, Fig. 1).
 #pragma once
-#include "wfst_device.h"
+#include "wfst_frame_general.h"
+#include "wfst_frame_light.h"
 
 namespace wfst {
 
-constexpr int NBINS = 1024;
-constexpr uint32_t F_NAN = 1, F_TOKOVF = 2, F_LATOVF = 4, F_RESTART = 8;
-constexpr uint32_t KEY_NONE = 0xFFFFFFFFu;
-constexpr uint32_t KEY_PINF = 0xFF800000u;    // okey(+inf)
-
-__device__ __forceinline__ uint32_t okey(float x) {
-  uint32_t b = __float_as_uint(x);
-  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-}
-__device__ __forceinline__ float key2f(uint32_t k) {
-  return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
-}
-__device__ __forceinline__ unsigned long long pack(uint32_t key, uint32_t arc) {
-  return ((unsigned long long)key << 32) | arc;
-}
-// Loads that bypass the per-CU vector cache: table words are updated by atomics, which
-// execute in L2, so cached copies could be stale.
-__device__ __forceinline__ uint32_t ld32(const uint32_t *p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ unsigned long long ld64(const unsigned long long *p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint32_t slot_hash(uint32_t handle, int hbits) {
-  return (handle * 2654435761u) >> (32 - hbits);
-}
-
-// Table words are read through these: in global memory with loads that bypass the per-CU
-// vector cache (see ld32), in LDS with plain loads.
-template <bool LDS> __device__ __forceinline__ uint32_t tl32(const uint32_t *p) { return LDS ? *p : ld32(p); }
-template <bool LDS> __device__ __forceinline__ unsigned long long tl64(const unsigned long long *p) { return LDS ? *p : ld64(p); }
-
-// Offer candidate K for state `handle`.  Returns the slot, or -1 if the table is full.
-template <bool LDS>
-__device__ __forceinline__ int ht_insert(Slot *slots, uint32_t mask, int hbits, uint32_t handle,
-                                         unsigned long long K, bool &claimed, bool &improved) {
-  uint32_t h = slot_hash(handle, hbits);
-  claimed = false; improved = false;
-  for (uint32_t probe = 0; probe <= mask; ++probe) {
-    // one compare-and-swap tells all three cases apart: free (now ours), ours already, another state's
-    uint32_t k = atomicCAS(&slots[h].handle, EMPTY, handle);
-    if (k == EMPTY) { claimed = true; k = handle; }
-    if (k == handle) {
-      unsigned long long old = atomicMin(&slots[h].val, K);
-      improved = K < old;
-      return (int)h;
-    }
-    h = (h + 1) & mask;
-  }
-  return -1;
-}
-// A whole slot at once: in LDS one 16-byte read instead of dependent 8- and 4-byte ones (a
-// reader beside concurrent atomic minima gets some value the slot held, which is all the
-// callers need); in global memory three independent coherent loads.
-template <bool LDS>
-__device__ __forceinline__ Slot ld_slot(const Slot *p) {
-  Slot r;
-  if (LDS) {
-    *reinterpret_cast<uint4 *>(&r) = *reinterpret_cast<const uint4 *>(p);
-  } else {
-    r.val = ld64(&p->val); r.handle = ld32(&p->handle); r.aux = ld32(&p->aux);
-  }
-  return r;
-}
-template <bool LDS>
-__device__ __forceinline__ int ht_find(const Slot *slots, uint32_t mask, int hbits, uint32_t handle) {
-  uint32_t h = slot_hash(handle, hbits);
-  for (uint32_t probe = 0; probe <= mask; ++probe) {
-    uint32_t k = tl32<LDS>(&slots[h].handle);
-    if (k == handle) return (int)h;
-    if (k == EMPTY) return -1;
-    h = (h + 1) & mask;
-  }
-  return -1;
-}
-
-// Small frames keep the state table in LDS; a frame that outgrows it is redone with the
-// lane's table in global memory (nothing is committed before the contraction stage).
-// A 512-thread lane shares its compute unit's 160 KB of LDS with another lane, a 1024-thread
-// lane has it to itself and takes a table, queue and limits twice as large.
-template <int NT> struct LdsCfg {
-  static constexpr int SLOTS = NT >= 1024 ? 8192 : 4096;
-  static constexpr int HBITS = NT >= 1024 ? 13 : 12;
-  static constexpr int CLAIM_LIMIT = SLOTS * 3 / 4;   // states touched in a frame
-  static constexpr int NIN_MAX = SLOTS / 4;           // tokens the frame starts from
-  static constexpr int QCAP = SLOTS;                  // entries of the LDS token queue (16-bit each)
-};
-constexpr int EXP_U = 4;                   // arcs per thread and round of the emitting expansion
-constexpr int EPS_U = 2;                   // epsilon arcs of a token fetched together
-constexpr int LAT_U = 4;                   // candidate records per thread and round of the lattice stage
-constexpr uint32_t AUX_EPS = 0x80000000u;  // Aux::slot flag: the record is an epsilon arc
-// Slot::aux while a frame is being built (afterwards: index of the kept token, or ~0):
-constexpr uint32_t A_FRESH = 0x80000000u;  // epsilon out-degree not counted yet
-constexpr uint32_t A_KEPT_MAX = 0x20000000u;  // aux < A_KEPT_MAX: index of the kept token
-// LDS queue entry: slot (up to 14 bits) | LQ_EPS | LQ_DUP
-constexpr uint32_t LQ_EPS = 0x4000u, LQ_DUP = 0x8000u, LQ_SLOT = 0x3FFFu;
-
-template <int NT>
-struct LaneShared {
-  int wave_tmp[NT / 64];
-  union {                      // the expansion's tile arrays and the selection's histogram never coexist
-    struct { int scan[NT]; float cost[NT]; uint32_t base[NT]; };
-    uint32_t hist[NBINS];
-  };
-  // queue entries (low word) and states claimed (high word) of the frame: one 64-bit counter,
-  // so that a claim takes one atomic for both
-  union { unsigned long long claim_ctr; struct { uint32_t qtail, nclaim; }; };
-  uint32_t auxn, best, flags, nvalid, nout, latn, kmin, kmax;
-  uint32_t sel_bin, sel_below, sel_cnt;
-  unsigned long long emit_arcs, eps_arcs;
-  // channel state, cached for the duration of the call
-  int status, nf, max_pre, max_post, iters_max, n_in;
-  long long in_off, hist_used, lat_room, lat_total, arcs_expanded;
-  long long lat_pos;           // ring position of record number lat_total
-  long long lat_head, lat_head_pos, blk_pos;   // first record not handed out, its ring position; seal scratch
-#ifdef WFST_PHASE_TIMING
-  unsigned long long ph[16], tlast, dbg_tok, dbg_iters, dbg_arcs;
-#endif
-  uint16_t lq[LdsCfg<NT>::QCAP];     // token queue of small frames
-  Slot table[LdsCfg<NT>::SLOTS];     // state table of small frames
-};
-
-#ifdef WFST_PHASE_TIMING
-#define PHASE_MARK(k) do { if (threadIdx.x == 0) { unsigned long long t_ = wall_clock64(); S.ph[k] += t_ - S.tlast; S.tlast = t_; } } while (0)
-#else
-#define PHASE_MARK(k) do { } while (0)
-#endif
-
-// Workgroup barrier for stages that communicate through LDS only: it orders LDS accesses but
-// does not wait for global loads or stores in flight, so the score-row touch and the stores of
-// notes / tokens / lattice records keep travelling across it.  With LOCAL false it is an
-// ordinary __syncthreads() (the global-table path communicates through global memory).
-template <bool LOCAL>
-__device__ __forceinline__ void wg_sync() {
-  if (LOCAL) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-  } else {
-    __syncthreads();
-  }
-}
-
-// One counter update per wavefront: the lanes that call this together (same call site,
-// any subset of the wave) get consecutive indices from a single atomic add.
-__device__ __forceinline__ uint32_t wave_alloc(uint32_t *counter) {
-  const unsigned long long m = __ballot(1);
-  const int lane = threadIdx.x & 63;
-  const int leader = __ffsll((long long)m) - 1;
-  uint32_t base = 0;
-  if (lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(m));
-  base = (uint32_t)__shfl((int)base, leader, 64);
-  return base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-}
-
-template <int NT, bool LOCAL = false>
-__device__ __forceinline__ int block_excl_scan(int v, int *s_wave, int &total) {
-  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
-  int inc = v;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    int t = __shfl_up(inc, d, 64);
-    if (lane >= d) inc += t;
-  }
-  if (lane == 63) s_wave[wid] = inc;
-  wg_sync<LOCAL>();
-  int base = 0, tot = 0;
-#pragma unroll
-  for (int i = 0; i < NT / 64; ++i) {
-    int t = s_wave[i];
-    if (i < wid) base += t;
-    tot += t;
-  }
-  wg_sync<LOCAL>();
-  total = tot;
-  return base + inc - v;
-}
-
-// The need-th smallest (1-based) of the values val(i, v) accepts, all known to lie in
-// [lo, hi]: theta, with the number of accepted values below it and equal to it.  Exact:
-// only integer histograms, refined until a bin is one value wide.
-template <int NT, class F>
-__device__ void block_select(LaneShared<NT> &S, int n, uint32_t need, uint32_t lo, uint32_t hi, F val,
-                             uint32_t &theta, uint32_t &n_less, uint32_t &n_eq) {
-  const int tid = threadIdx.x;
-  constexpr int PER = NBINS / NT;
-  uint32_t less = 0;
-  for (;;) {
-    int shift = 0;                           // bins of 2^shift values: the last value, hi, must fall into bin NBINS - 1 at most
-    while ((((unsigned long long)hi - lo) >> shift) >= (unsigned long long)NBINS) ++shift;
-    for (int b = tid; b < NBINS; b += NT) S.hist[b] = 0;
-    __syncthreads();
-    for (int i = tid; i < n; i += NT) {
-      uint32_t v;
-      if (val(i, v) && v >= lo && v <= hi) atomicAdd(&S.hist[(v - lo) >> shift], 1u);
-    }
-    __syncthreads();
-    uint32_t loc[PER], sum = 0;
-#pragma unroll
-    for (int q = 0; q < PER; ++q) { loc[q] = S.hist[tid * PER + q]; sum += loc[q]; }
-    int total;
-    uint32_t run = (uint32_t)block_excl_scan<NT>((int)sum, S.wave_tmp, total);
-#pragma unroll
-    for (int q = 0; q < PER; ++q) {
-      if (run < need && run + loc[q] >= need) { S.sel_bin = tid * PER + q; S.sel_below = run; S.sel_cnt = loc[q]; }
-      run += loc[q];
-    }
-    __syncthreads();
-    const uint32_t b = S.sel_bin, below = S.sel_below, cnt = S.sel_cnt;
-    __syncthreads();
-    less += below;
-    need -= below;
-    lo = lo + (b << shift);
-    unsigned long long nhi = (unsigned long long)lo + ((1ull << shift) - 1);
-    if (nhi < hi) hi = (uint32_t)nhi;
-    if (shift == 0) { theta = lo; n_less = less; n_eq = cnt; return; }
-  }
-}
-
-// One frame of one lane.  LDS: the state table lives in S.table (small frames), otherwise in
-// the lane's global table.  Returns false (LDS mode only) if the frame outgrew the LDS table
-// and must be redone with the global one; nothing has been committed in that case.
-template <int NT, bool LDS>
-__device__ bool lane_frame(const DecDev &D, LaneShared<NT> &S, const float *ll, bool is_init,
-                           Slot *gslots, uint32_t *queue, Aux *aux, uint32_t *dkey, uint32_t *dslot,
-                           long long *foff, HTok *hist, LatInt *lat) {
-  const int tid = threadIdx.x;
-  const uint32_t *rec = D.g.rec;
-  Slot *slots = LDS ? S.table : gslots;
-  const uint32_t mask = LDS ? (uint32_t)(LdsCfg<NT>::SLOTS - 1) : D.H - 1;
-  const int hbits = LDS ? LdsCfg<NT>::HBITS : D.hbits;
-  const Slot fresh{~0ull, EMPTY, A_FRESH};
-
-  if (tid == 0) {
-    S.qtail = 0; S.nclaim = 0; S.auxn = 0; S.best = KEY_NONE; S.flags = 0; S.nvalid = 0; S.nout = 0; S.latn = 0;
-    S.kmin = 0xFFFFFFFFu; S.kmax = 0; S.emit_arcs = 0; S.eps_arcs = 0;
-  }
-  wg_sync<LDS>();
-  const int nf = S.nf;                       // index of the frame being written
-  const long long out_base = S.hist_used;
-  int abort_code = 0;
-  if (nf > D.max_frames) abort_code = E_HISTORY_OVERFLOW;
-
-  // the frame's token queue: claimed slots, plus re-expansion requests for improved ones
-  const uint32_t qcap = LDS ? (uint32_t)LdsCfg<NT>::QCAP : (uint32_t)D.qcap;
-  auto qget = [&](uint32_t i, uint32_t &sl, bool &eps, bool &dup) {
-    if (LDS) { const uint32_t e = S.lq[i]; sl = e & LQ_SLOT; eps = e & LQ_EPS; dup = e & LQ_DUP; }
-    else { const uint32_t e = queue[i]; sl = e & Q_SLOT; eps = e & Q_EPS; dup = e & Q_DUP; }
-  };
-  auto on_claim = [&](int sl, uint32_t dw, bool dup) {
-    // the lanes of the wave that call this together get consecutive queue entries and, those
-    // that claimed a new state, consecutive claim numbers, from a single 64-bit atomic add
-    const unsigned long long m_all = __ballot(1), m_new = __ballot(!dup);
-    const int wl = threadIdx.x & 63, leader = __ffsll((long long)m_all) - 1;
-    unsigned long long base = 0;
-    if (wl == leader) base = atomicAdd(&S.claim_ctr, ((unsigned long long)__popcll(m_new) << 32) | (unsigned long long)__popcll(m_all));
-    base = __shfl(base, leader, 64);
-    const unsigned long long below = (1ull << wl) - 1ull;
-    if (!dup) {
-      const uint32_t ci = (uint32_t)(base >> 32) + (uint32_t)__popcll(m_new & below);
-      if (ci >= (uint32_t)D.tokcap) atomicOr(&S.flags, F_TOKOVF);
-      else if (LDS && ci >= (uint32_t)LdsCfg<NT>::CLAIM_LIMIT) atomicOr(&S.flags, F_RESTART);
-    }
-    const uint32_t q = (uint32_t)base + (uint32_t)__popcll(m_all & below);
-    if (q >= qcap) atomicOr(&S.flags, LDS ? F_RESTART : F_TOKOVF);
-    else if (LDS) S.lq[q] = (uint16_t)((uint32_t)sl | ((dw & HAS_EPS) ? LQ_EPS : 0u) | (dup ? LQ_DUP : 0u));
-    else queue[q] = (uint32_t)sl | ((dw & HAS_EPS) ? Q_EPS : 0u) | (dup ? Q_DUP : 0u);
-  };
-
-  // ---- 1. emitting expansion ------------------------------------------------------------
-  if (abort_code == 0) {
-    if (is_init) {
-      if (tid == 0) {
-        const uint32_t h = D.g.start_handle;
-        bool cl, im;
-        const int sl = ht_insert<LDS>(slots, mask, hbits, h, pack(okey(0.0f), NO_ARC), cl, im);
-        on_claim(sl, rec[3 * (size_t)h + 1] ? HAS_EPS : 0u, false);
-        S.best = okey(0.0f);
-      }
-    } else {
-      const long long in_off = S.in_off;
-      const int n_in = S.n_in;
-      // touch this frame's row of scores (one 64-byte line per thread) while the tokens'
-      // graph records are being fetched, so that the gathers by pdf id below hit L2
-      const float touch = tid * 16 < D.g.num_pdfs ? ll[tid * 16] : 0.f;
-      float touch_more = 0.f;
-      for (int p = (NT + tid) * 16; p < D.g.num_pdfs; p += NT * 16) touch_more += ll[p];
-      // this thread's token of a tile: state handle, cost, emitting out-degree
-      auto load_token = [&](int i, uint32_t &h, float &c, int &ne) {
-        ne = 0; h = 0; c = 0.f;
-        if (i < n_in) {
-          const HTok t = hist[in_off + i];
-          h = t.handle & HMASK; c = t.cost;
-          ne = (int)rec[3 * (size_t)h];
-        }
-      };
-      uint32_t h, hn = 0; float c, cn = 0.f; int ne, nen = 0;
-      load_token(tid, h, c, ne);
-      for (int tb = 0; tb < n_in; tb += NT) {
-        int total;
-        const int ex = block_excl_scan<NT, LDS>(ne, S.wave_tmp, total);
-        S.scan[tid] = ex; S.cost[tid] = c; S.base[tid] = h + 1;
-        wg_sync<LDS>();
-        PHASE_MARK(8);
-        if (tid == 0) S.emit_arcs += (unsigned long long)total;
-        if (tb + NT < n_in) load_token(tb + NT + tid, hn, cn, nen);   // next tile, in flight during this one's rounds
-        // one thread per arc (Section 3.3), EXP_U arcs of the tile per thread and round so
-        // that their loads are in flight together
-        for (int j0 = 0; j0 < total; j0 += NT * EXP_U) {
-          float x[EXP_U], cw[EXP_U]; uint32_t r[EXP_U], dw[EXP_U], kx[EXP_U], pdf[EXP_U]; int kk[EXP_U];
-#pragma unroll
-          for (int u = 0; u < EXP_U; ++u) {
-            const int j = j0 + u * NT + tid;
-            kx[u] = KEY_NONE; kk[u] = -1; r[u] = 0; dw[u] = 0; pdf[u] = 0; cw[u] = 0.f; x[u] = 0.f;
-            if (j < total) {
-              int lo = 0, hi = NT - 1;             // largest k with scan[k] <= j
-              while (lo < hi) { int mid = (lo + hi + 1) >> 1; if (S.scan[mid] <= j) lo = mid; else hi = mid - 1; }
-              kk[u] = lo;
-              r[u] = S.base[lo] + (uint32_t)(j - S.scan[lo]);
-              const uint32_t *a = rec + 3 * (size_t)r[u];
-              dw[u] = a[0];
-              cw[u] = S.cost[lo] + __uint_as_float(a[1]);
-              pdf[u] = a[2];
-            }
-          }
-          uint32_t m = KEY_NONE;
-#pragma unroll
-          for (int u = 0; u < EXP_U; ++u) {
-            if (kk[u] >= 0) {
-              x[u] = cw[u] - ll[pdf[u]];
-              if (x[u] != x[u] || x[u] == -INFINITY) atomicOr(&S.flags, F_NAN); else kx[u] = okey(x[u]);
-              m = min(m, kx[u]);
-            }
-          }
-#pragma unroll
-          for (int d = 32; d; d >>= 1) m = min(m, (uint32_t)__shfl_xor((int)m, d, 64));
-          if ((tid & 63) == 0 && m != KEY_NONE) atomicMin(&S.best, m);
-          wg_sync<LDS>();
-          PHASE_MARK(9);
-          const float cut = key2f(S.best) + D.beam;     // running bound, never below the final cutoff
-#pragma unroll
-          for (int u = 0; u < EXP_U; ++u) {
-            if (kx[u] == KEY_NONE || !(x[u] <= cut)) continue;
-            bool cl, im;
-            const int sl = ht_insert<LDS>(slots, mask, hbits, dw[u] & HMASK, pack(kx[u], r[u]), cl, im);
-            if (sl < 0) { atomicOr(&S.flags, LDS ? F_RESTART : F_TOKOVF); continue; }
-            if (cl) on_claim(sl, dw[u], false);
-            if (D.lattice_on || im) {
-              const uint32_t ai = wave_alloc(&S.auxn);
-              if (ai >= (uint32_t)D.auxcap) atomicOr(&S.flags, F_LATOVF);
-              else aux[ai] = Aux{(uint32_t)sl, x[u], r[u], (uint32_t)(tb + kk[u])};
-            }
-          }
-        }
-        wg_sync<LDS>();
-        PHASE_MARK(10);
-        h = hn; c = cn; ne = nen;
-      }
-      asm volatile("" ::"v"(touch), "v"(touch_more));
-    }
-  }
-  wg_sync<LDS>();
-  PHASE_MARK(0);
-  const uint32_t bestk = S.best;
-  if (abort_code == 0) {
-    const uint32_t fl = S.flags;
-    if (fl & F_NAN) abort_code = E_NAN_INPUT;
-    else if (fl & F_TOKOVF) abort_code = E_TOKEN_OVERFLOW;
-    else if (fl & F_LATOVF) abort_code = E_LATTICE_OVERFLOW;
-    else if (bestk == KEY_NONE || bestk == KEY_PINF) abort_code = E_DEAD_CHANNEL;
-  }
-  const float cutoff = key2f(bestk) + D.beam;
-
-  // ---- 2. non-emitting closure ----------------------------------------------------------
-  // One epsilon arc of an expanded token: note it for the lattice stage on the token's first
-  // expansion (source slot, weight, arc, destination), then offer the candidate.
-  auto relax_eps = [&](uint32_t src_slot, float c, uint32_t r, uint32_t dw, float w, uint32_t note_at) {
-    if (note_at < (uint32_t)D.auxcap) aux[note_at] = Aux{src_slot | AUX_EPS, w, r, dw & HMASK};
-    const float x = c + w;
-    if (!(x <= cutoff)) return;
-    bool cl, im;
-    const int sl = ht_insert<LDS>(slots, mask, hbits, dw & HMASK, pack(okey(x), r), cl, im);
-    if (sl < 0) { atomicOr(&S.flags, LDS ? F_RESTART : F_TOKOVF); return; }
-    if (cl || im) on_claim(sl, dw, !cl);
-  };
-  int iters = 0;
-  if (abort_code == 0 && !(LDS && (S.flags & F_RESTART))) {
-    uint32_t w0 = 0, w1 = min(S.qtail, qcap);
-    wg_sync<LDS>();
-    while (w0 < w1) {
-      // every thread takes one queue entry of the window per pass; the pass is kept convergent
-      // (predicated, no early exit) so that the wave can allot note space with one atomic
-      for (uint32_t i0 = w0; i0 < w1; i0 += NT) {
-        const uint32_t i = i0 + tid;
-        bool act = false; uint32_t src = 0; float c = 0.f;
-        uint32_t h = 0, ne = 0, np = 0; bool first = false;
-        if (i < w1) {
-          bool eps, dup;
-          qget(i, src, eps, dup);
-          if (eps) {
-            const Slot sv = ld_slot<LDS>(&slots[src]);
-            c = key2f((uint32_t)(sv.val >> 32)); act = c <= cutoff; h = sv.handle;
-          }
-        }
-        if (act) {
-          ne = rec[3 * (size_t)h]; np = rec[3 * (size_t)h + 1];
-          first = atomicAnd(&slots[src].aux, ~A_FRESH) & A_FRESH;   // first expansion while within the cutoff
-        }
-        uint32_t dwv[EPS_U]; float wv[EPS_U];                        // the first arcs, loads in flight together
-#pragma unroll
-        for (int k = 0; k < EPS_U; ++k) {
-          dwv[k] = 0; wv[k] = 0.f;
-          if (act && (uint32_t)k < np) {
-            const uint32_t *a = rec + 3 * (size_t)(h + 1 + ne + k);
-            dwv[k] = a[0]; wv[k] = __uint_as_float(a[1]);
-          }
-        }
-        // note space and the arc count, one atomic per wave
-        const uint32_t nn = first ? np : 0u;
-        uint32_t inc = nn;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) { const uint32_t t = (uint32_t)__shfl_up((int)inc, d, 64); if ((tid & 63) >= d) inc += t; }
-        const uint32_t wave_total = (uint32_t)__shfl((int)inc, 63, 64);
-        uint32_t note = 0;
-        if ((tid & 63) == 0 && wave_total) {
-          note = atomicAdd(&S.auxn, wave_total);
-          atomicAdd(&S.eps_arcs, (unsigned long long)wave_total);
-          if (note + wave_total > (uint32_t)D.auxcap) atomicOr(&S.flags, F_LATOVF);
-        }
-        note = (uint32_t)__shfl((int)note, 0, 64) + inc - nn;
-#pragma unroll
-        for (int k = 0; k < EPS_U; ++k)
-          if (act && (uint32_t)k < np) relax_eps(src, c, h + 1 + ne + k, dwv[k], wv[k], first ? note + k : 0xFFFFFFFFu);
-        for (uint32_t k = EPS_U; act && k < np; ++k) {
-          const uint32_t *a = rec + 3 * (size_t)(h + 1 + ne + k);
-          relax_eps(src, c, h + 1 + ne + k, a[0], __uint_as_float(a[1]), first ? note + k : 0xFFFFFFFFu);
-        }
-      }
-      wg_sync<LDS>();
-      PHASE_MARK(11);
-      w0 = w1; w1 = min(S.qtail, qcap);
-      ++iters;
-      wg_sync<LDS>();
-    }
-    if (S.flags & F_TOKOVF) abort_code = E_TOKEN_OVERFLOW;
-    else if (S.flags & F_LATOVF) abort_code = E_LATTICE_OVERFLOW;
-  }
-  PHASE_MARK(1);
-  if (LDS) {
-    wg_sync<true>();
-    if (abort_code == 0 && (S.flags & F_RESTART)) {     // outgrew the LDS table: wipe it, redo with the global one
-      for (int i = tid; i < LdsCfg<NT>::SLOTS; i += NT) slots[i] = fresh;
-      __syncthreads();
-      return false;
-    }
-  }
-  const uint32_t n_q = min(S.qtail, qcap);
-  auto token_slot = [&](uint32_t i, uint32_t &sl, uint32_t &eps) -> bool {
-    bool e, dup;
-    qget(i, sl, e, dup);
-    eps = e;
-    return !dup;
-  };
-
-  // ---- 3 + 4. max-active selection and contraction into the token history ---------------
-  float cutoff_eff = cutoff;
-  if (abort_code == 0) {
-    const uint32_t nclaim = S.nclaim;
-    const uint32_t room = (uint32_t)min((long long)0x7FFFFFFF, D.hist_cap - out_base);
-    if (min(nclaim, (uint32_t)D.max_active) > room) abort_code = E_HISTORY_OVERFLOW;
-    else if (nclaim <= (uint32_t)D.max_active) {
-      // nothing can be pruned: every token within the beam is kept
-      for (uint32_t i = tid; i < n_q; i += NT) {
-        uint32_t sl, eps;
-        if (!token_slot(i, sl, eps)) continue;
-        Slot *sp = slots + sl;
-        const Slot sv = ld_slot<LDS>(sp);
-        const unsigned long long v = sv.val;
-        const float c = key2f((uint32_t)(v >> 32));
-        if (!(c <= cutoff)) continue;
-        const uint32_t pos = wave_alloc(&S.nout);
-        if (pos >= room) continue;
-        hist[out_base + pos] = HTok{sv.handle | (eps ? HAS_EPS : 0u), c, (uint32_t)v, NO_ARC};
-        sp->aux = pos;
-      }
-      wg_sync<LDS>();
-      if (tid == 0) S.nvalid = S.nout;
-    } else {
-      for (uint32_t i = tid; i < n_q; i += NT) {
-        uint32_t sl, eps;
-        if (!token_slot(i, sl, eps)) continue;
-        const uint32_t key = (uint32_t)(tl64<LDS>(&slots[sl].val) >> 32);
-        if (!(key2f(key) <= cutoff)) continue;
-        const uint32_t p = wave_alloc(&S.nvalid);
-        dkey[p] = key; dslot[p] = sl | (eps ? Q_EPS : 0u);
-        atomicMin(&S.kmin, key); atomicMax(&S.kmax, key);
-      }
-      __syncthreads();
-      const int n = (int)S.nvalid;
-      uint32_t theta = KEY_NONE, h_theta = 0xFFFFFFFFu;       // keep key < theta, or == theta with handle <= h_theta
-      if (n > D.max_active) {
-        uint32_t n_less, n_eq;
-        block_select<NT>(S, n, (uint32_t)D.max_active, S.kmin, S.kmax,
-                         [&](int i, uint32_t &v) { v = dkey[i]; return true; }, theta, n_less, n_eq);
-        const uint32_t need_eq = (uint32_t)D.max_active - n_less;
-        if (need_eq < n_eq) {
-          uint32_t hl, he;
-          block_select<NT>(S, n, need_eq, 0u, HMASK,
-                           [&](int i, uint32_t &v) {
-                             if (dkey[i] != theta) return false;
-                             v = tl32<LDS>(&slots[dslot[i] & Q_SLOT].handle);
-                             return true;
-                           }, h_theta, hl, he);
-        }
-        cutoff_eff = key2f(theta);
-      }
-      for (int i = tid; i < n; i += NT) {
-        const uint32_t key = dkey[i], ds = dslot[i];
-        Slot *sp = slots + (ds & Q_SLOT);
-        const uint32_t h = tl32<LDS>(&sp->handle);
-        const bool keep = key < theta || (key == theta && h <= h_theta);
-        uint32_t pos = 0xFFFFFFFFu;
-        if (keep) pos = wave_alloc(&S.nout);
-        if (pos < room) {
-          hist[out_base + pos] = HTok{h | ((ds & Q_EPS) ? HAS_EPS : 0u), key2f(key), (uint32_t)tl64<LDS>(&sp->val), NO_ARC};
-          sp->aux = pos;
-        } else {
-          sp->aux = 0xFFFFFFFFu;
-        }
-      }
-    }
-  }
-  __syncthreads();
-  PHASE_MARK(2);
-  const uint32_t n_out = (abort_code == 0) ? min(S.nout, (uint32_t)D.max_active) : 0u;
-
-  // ---- 5. lattice records and back-pointers ---------------------------------------------
-  if (abort_code == 0) {
-    const long long lat_base = S.lat_pos;
-    const uint32_t n_aux = min(S.auxn, (uint32_t)D.auxcap);
-    auto emit_lat = [&](uint32_t arc, float extra, uint32_t dst, uint32_t src) {
-      const uint32_t p = wave_alloc(&S.latn);
-      if ((long long)p >= S.lat_room) atomicOr(&S.flags, F_LATOVF);
-      else {
-        long long at = lat_base + (long long)p;
-        if (at >= D.lat_cap) at -= D.lat_cap;
-        lat[at] = LatInt{nf, arc, extra, dst, src};
-      }
-    };
-    for (uint32_t i0 = 0; i0 < n_aux; i0 += NT * LAT_U) {
-      Aux a[LAT_U];
-#pragma unroll
-      for (int u = 0; u < LAT_U; ++u) {
-        const uint32_t i = i0 + u * NT + tid;
-        a[u] = i < n_aux ? aux[i] : Aux{0xFFFFFFFFu, 0.f, 0u, 0u};
-      }
-#pragma unroll
-      for (int u = 0; u < LAT_U; ++u) {
-        if (a[u].slot == 0xFFFFFFFFu) continue;
-        if (!(a[u].slot & AUX_EPS)) {
-          // emitting candidate {slot of the destination, x, arc, index of the source token}
-          const Slot sv = ld_slot<LDS>(slots + a[u].slot);
-          const uint32_t pos = sv.aux;
-          if (pos >= A_KEPT_MAX) continue;
-          const unsigned long long v = sv.val;
-          if (pack(okey(a[u].x), a[u].arc) == v) hist[out_base + pos].prev = a[u].src;
-          if (D.lattice_on && a[u].x <= cutoff_eff) {
-            const float extra = a[u].x - key2f((uint32_t)(v >> 32));
-            if (extra <= D.lattice_beam) emit_lat(a[u].arc, extra, pos, a[u].src);
-          }
-        } else {
-          // epsilon arc {slot of the source | AUX_EPS, weight, arc, handle of the destination}
-          const Slot ssv = ld_slot<LDS>(slots + (a[u].slot & ~AUX_EPS));
-          const uint32_t spos = ssv.aux;
-          if (spos >= A_KEPT_MAX) continue;                        // the source token was not kept
-          const float x = key2f((uint32_t)(ssv.val >> 32)) + a[u].x;
-          if (!(x <= cutoff_eff)) continue;
-          const int sl = ht_find<LDS>(slots, mask, hbits, a[u].src);
-          if (sl < 0) continue;
-          const Slot sv = ld_slot<LDS>(slots + sl);
-          const uint32_t pos = sv.aux;
-          if (pos >= A_KEPT_MAX) continue;
-          const unsigned long long v = sv.val;
-          if (pack(okey(x), a[u].arc) == v) hist[out_base + pos].prev = spos | PREV_SAME;
-          if (D.lattice_on) {
-            const float extra = x - key2f((uint32_t)(v >> 32));
-            if (extra <= D.lattice_beam) emit_lat(a[u].arc, extra, pos, spos | PREV_SAME);
-          }
-        }
-      }
-    }
-  }
-  wg_sync<LDS>();
-  PHASE_MARK(3);
-
-  // ---- 6. clear the table ---------------------------------------------------------------
-  if (S.flags & F_TOKOVF) {                                        // untracked claims: wipe everything
-    const uint32_t n_all = LDS ? (uint32_t)LdsCfg<NT>::SLOTS : D.H;
-    for (uint32_t i = tid; i < n_all; i += NT) slots[i] = fresh;
-  } else {
-    for (uint32_t i = tid; i < n_q; i += NT) {
-      uint32_t sl, eps;
-      if (token_slot(i, sl, eps)) slots[sl] = fresh;
-    }
-  }
-  if (tid == 0) {
-    if (abort_code == 0 && (S.flags & F_LATOVF)) abort_code = E_LATTICE_OVERFLOW;
-    const long long lat_new = min((long long)S.latn, S.lat_room);
-    if (nf <= D.max_frames) {
-      foff[nf + 1] = out_base + n_out;
-      S.nf = nf + 1;
-      S.in_off = out_base; S.n_in = (int)n_out;      // the frame just written is what the next one expands
-    }
-    S.hist_used = out_base + n_out;
-    S.lat_total += lat_new; S.lat_room -= lat_new;
-    S.lat_pos += lat_new;
-    if (S.lat_pos >= D.lat_cap) S.lat_pos -= D.lat_cap;
-    S.arcs_expanded += (long long)(S.emit_arcs + S.eps_arcs);
-    S.max_pre = max(S.max_pre, (int)S.nvalid);
-    S.max_post = max(S.max_post, (int)n_out);
-    S.iters_max = max(S.iters_max, iters);
-#ifdef WFST_PHASE_TIMING
-    S.ph[7] += iters; S.dbg_tok += n_out; S.dbg_iters += iters; S.dbg_arcs += S.emit_arcs + S.eps_arcs;
-#endif
-    if (abort_code != 0) S.status = abort_code;
-  }
-  wg_sync<LDS>();
-  PHASE_MARK(4);
-  return true;
-}
-
 // One workgroup per lane.  is_init: (re)start the lane's channel and write frame 0.
+// Between frames the lane's state is held in registers by every thread (LaneCtx, all values
+// uniform); a general frame gets it through LDS.
 template <int NT>
-__global__ void __launch_bounds__(NT, 4) k_advance(DecDev D, const LaneParam *__restrict__ lanes, int is_init) {
+__global__ void __launch_bounds__(NT, NT >= 512 ? 4 : 2) k_advance(DecDev D, const LaneParam *__restrict__ lanes, int is_init) {
   __shared__ LaneShared<NT> S;
   const int tid = threadIdx.x;
   const LaneParam lp = lanes[blockIdx.x];
@@ -681,31 +53,33 @@ __global__ void __launch_bounds__(NT, 4) k_advance(DecDev D, const LaneParam *__
   HTok *hist = D.hist + (size_t)lp.chan * (size_t)D.hist_cap;
   LatInt *lat = D.lat + (size_t)lp.chan * (size_t)D.lat_cap;
 
-  const Slot fresh{~0ull, EMPTY, A_FRESH};
-  for (int i = tid; i < LdsCfg<NT>::SLOTS; i += NT) S.table[i] = fresh;
+  const Slot fresh{~0ull, EMPTY, 0xFFFFFFFFu};
+  for (int i = tid; i < LightCfg<NT>::SLOTS; i += NT) S.table[i] = fresh;
   if (tid == 0) {
-    if (is_init) {
-      S.status = 0; S.nf = 0; S.hist_used = 0; S.lat_room = D.lat_cap; S.lat_pos = 0; S.lat_total = 0; S.arcs_expanded = 0;
-      S.lat_head = 0; S.lat_head_pos = 0;
-      S.max_pre = 0; S.max_post = 0; S.iters_max = 0;
-      foff[0] = 0;
-    } else {
-      S.status = cs->status; S.nf = cs->num_frames; S.hist_used = cs->hist_used;
-      S.lat_head = cs->lat_head;
-      S.lat_room = D.lat_cap - (cs->lat_total - S.lat_head);
-      S.lat_pos = cs->lat_total % D.lat_cap;
-      S.lat_head_pos = S.lat_head % D.lat_cap;
-      S.lat_total = cs->lat_total; S.arcs_expanded = cs->arcs_expanded; S.max_pre = cs->max_pre;
-      S.max_post = cs->max_post; S.iters_max = cs->closure_iters_max;
-    }
-    S.in_off = 0; S.n_in = 0;
-    if (!is_init && S.nf >= 1 && S.nf <= D.max_frames + 1) { S.in_off = foff[S.nf - 1]; S.n_in = (int)(foff[S.nf] - foff[S.nf - 1]); }
+    reset_ctr(S.fc[0]); reset_ctr(S.fc[1]);
+    if (is_init) foff[0] = 0;
 #ifdef WFST_PHASE_TIMING
     for (int k = 0; k < 16; ++k) S.ph[k] = 0;
     S.dbg_tok = 0; S.dbg_iters = 0; S.dbg_arcs = 0;
     S.tlast = wall_clock64();
 #endif
   }
+  LaneCtx ctx;
+  if (is_init) {
+    ctx.status = 0; ctx.nf = 0; ctx.hist_used = 0; ctx.lat_room = D.lat_cap; ctx.lat_pos = 0; ctx.lat_total = 0;
+    ctx.arcs_expanded = 0; ctx.lat_head = 0; ctx.lat_head_pos = 0; ctx.max_pre = 0; ctx.max_post = 0; ctx.iters_max = 0;
+  } else {
+    ctx.status = cs->status; ctx.nf = cs->num_frames; ctx.hist_used = cs->hist_used;
+    ctx.lat_head = cs->lat_head; ctx.lat_total = cs->lat_total;
+    ctx.lat_room = D.lat_cap - (ctx.lat_total - ctx.lat_head);
+    ctx.lat_pos = ctx.lat_total % D.lat_cap;
+    ctx.lat_head_pos = ctx.lat_head % D.lat_cap;
+    ctx.arcs_expanded = cs->arcs_expanded; ctx.max_pre = cs->max_pre;
+    ctx.max_post = cs->max_post; ctx.iters_max = cs->closure_iters_max;
+  }
+  ctx.in_off = 0; ctx.n_in = 0;
+  if (!is_init && ctx.nf >= 1 && ctx.nf <= D.max_frames + 1) { ctx.in_off = foff[ctx.nf - 1]; ctx.n_in = (int)(foff[ctx.nf] - foff[ctx.nf - 1]); }
+  ctx.pending_clear = 0; ctx.par = 0; ctx.tok_valid = false;
   __syncthreads();
   // Seal the lane's state as the next snapshot of this call.  With snapshot blocks the lattice
   // records not handed out yet move into the snapshot's block, in the caller's form (the lane
@@ -715,12 +89,12 @@ __global__ void __launch_bounds__(NT, 4) k_advance(DecDev D, const LaneParam *__
   // the host has seen the progress words of all lanes, so nothing ever waits inside a kernel.
   int n_sealed = 0;
   auto seal = [&]() {
-    __syncthreads();                                  // all waves' stores have been issued and acknowledged
+    __syncthreads();                                  // every wave has issued its stores of the frames so far
     const long long id = lp.snap_id0 + n_sealed;
     long long blk_start = 0, blk_count = 0;
     if (D.n_blk > 0 && D.lattice_on) {
       const int slot = (int)(id % D.n_blk);
-      const long long n = S.lat_total - S.lat_head;
+      const long long n = ctx.lat_total - ctx.lat_head;
       if (tid == 0) {
         unsigned long long *used = &D.blk[slot].used;
         unsigned long long old = ld64(used);
@@ -730,14 +104,14 @@ __global__ void __launch_bounds__(NT, 4) k_advance(DecDev D, const LaneParam *__
           if (seen == old) { pos = (long long)old; break; }
           old = seen;
         }
-        if (pos < 0 && S.status == 0) S.status = E_LATTICE_OVERFLOW;
         S.blk_pos = pos;
       }
       __syncthreads();
       const long long pos = S.blk_pos;
+      if (pos < 0 && ctx.status == 0) ctx.status = E_LATTICE_OVERFLOW;
       if (pos >= 0) {
         LatRec *out = D.blk_recs + (size_t)slot * (size_t)D.blk_cap + (size_t)pos;
-        const long long first = S.lat_head_pos;
+        const long long first = ctx.lat_head_pos;
         constexpr int U = 8;                            // records per thread in flight: the arc-id gathers are HBM round trips
         for (long long i0 = tid; i0 < n; i0 += (long long)NT * U) {
           LatInt r[U];
@@ -759,34 +133,55 @@ __global__ void __launch_bounds__(NT, 4) k_advance(DecDev D, const LaneParam *__
         }
         blk_start = pos; blk_count = n;
       }
-      __syncthreads();
-      if (tid == 0) { S.lat_head = S.lat_total; S.lat_head_pos = S.lat_pos; S.lat_room = D.lat_cap; }
+      ctx.lat_head = ctx.lat_total; ctx.lat_head_pos = ctx.lat_pos; ctx.lat_room = D.lat_cap;
     }
+    // every thread's stores (tokens, lattice records, the block) must have reached device
+    // memory before the snapshot is published: each thread releases its own, then the barrier,
+    // then thread 0 publishes with a system-scope release
+    __threadfence();
+    __syncthreads();
     if (tid == 0) {
       ChanSnap *sp = D.snap + (size_t)lp.chan * SNAP_RING + (size_t)(id % SNAP_RING);
-      sp->lat_total = S.lat_total; sp->hist_used = S.hist_used; sp->status = S.status; sp->num_frames = S.nf;
+      sp->lat_total = ctx.lat_total; sp->hist_used = ctx.hist_used; sp->status = ctx.status; sp->num_frames = ctx.nf;
       sp->blk_start = blk_start; sp->blk_count = blk_count;
       sp->id = id;
       __hip_atomic_store(D.lane_sealed + blockIdx.x, id, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     }
     ++n_sealed;
   };
+  // a frame in the general form: the lane's state goes through LDS
+  auto run_general = [&](const float *ll) {
+    if (tid == 0) {
+      S.status = ctx.status; S.nf = ctx.nf; S.n_in = ctx.n_in; S.max_pre = ctx.max_pre; S.max_post = ctx.max_post;
+      S.iters_max = ctx.iters_max; S.in_off = ctx.in_off; S.hist_used = ctx.hist_used; S.lat_room = ctx.lat_room;
+      S.lat_total = ctx.lat_total; S.lat_pos = ctx.lat_pos; S.arcs_expanded = ctx.arcs_expanded;
+    }
+    __syncthreads();                                  // (also: the light frames' history stores have arrived)
+    general_frame<NT>(D, S, ll, is_init != 0, slots, queue, aux, dkey, dslot, foff, hist, lat);
+    ctx.status = S.status; ctx.nf = S.nf; ctx.n_in = S.n_in; ctx.max_pre = S.max_pre; ctx.max_post = S.max_post;
+    ctx.iters_max = S.iters_max; ctx.in_off = S.in_off; ctx.hist_used = S.hist_used; ctx.lat_room = S.lat_room;
+    ctx.lat_total = S.lat_total; ctx.lat_pos = S.lat_pos; ctx.arcs_expanded = S.arcs_expanded;
+    ctx.tok_valid = false;
+    __syncthreads();                                  // all have read the state before the next general frame rewrites it
+  };
   const int nframes = is_init ? 1 : lp.n_frames;
   const int n_snaps = is_init ? 0 : lp.n_snaps;
+  const bool light_ok = D.g.info_shift != 0 && D.force_general == 0;
   int until_seal = (!is_init && lp.snap_every > 0) ? lp.snap_every : 0x7FFFFFFF;
   for (int f = 0;;) {
-    const bool more = f < nframes && S.status == 0;
+    const bool more = f < nframes && ctx.status == 0;
     if (more) {
       const float *ll = is_init ? nullptr : lp.ll + (size_t)f * (size_t)lp.stride;
-      bool small = is_init != 0;
-      if (!small) small = S.n_in <= LdsCfg<NT>::NIN_MAX;
+      const float *ll_next = (!is_init && f + 1 < nframes) ? ll + lp.stride : nullptr;
       bool done = false;
-      if (small) done = lane_frame<NT, true>(D, S, ll, is_init != 0, slots, queue, aux, dkey, dslot, foff, hist, lat);
+      if (light_ok && (is_init || ctx.n_in <= LightCfg<NT>::NIN_MAX))
+        done = light_frame<NT>(D, S, ctx, ll, ll_next, is_init != 0, aux, dkey, dslot, foff, hist, lat);
       if (!done) {
 #ifdef WFST_PHASE_TIMING
-        if (tid == 0 && small) S.ph[6] += 1;
+        if (tid == 0) S.ph[6] += 1;
 #endif
-        lane_frame<NT, false>(D, S, ll, is_init != 0, slots, queue, aux, dkey, dslot, foff, hist, lat);
+        run_general(ll);
+        PHASE_MARK(11);
       }
 #ifdef WFST_PHASE_TIMING
       if (tid == 0) S.ph[5] += 1;
@@ -803,23 +198,19 @@ __global__ void __launch_bounds__(NT, 4) k_advance(DecDev D, const LaneParam *__
   }
   __syncthreads();
   if (tid == 0) {
-    cs->status = S.status; cs->num_frames = S.nf; cs->hist_used = S.hist_used;
-    cs->lat_total = S.lat_total; cs->arcs_expanded = S.arcs_expanded; cs->max_pre = S.max_pre;
-    cs->max_post = S.max_post; cs->closure_iters_max = S.iters_max;
+    cs->status = ctx.status; cs->num_frames = ctx.nf; cs->hist_used = ctx.hist_used;
+    cs->lat_total = ctx.lat_total; cs->arcs_expanded = ctx.arcs_expanded; cs->max_pre = ctx.max_pre;
+    cs->max_post = ctx.max_post; cs->closure_iters_max = ctx.iters_max;
     if (is_init) cs->path_nf = 0;
-    cs->lat_head = S.lat_head;
+    cs->lat_head = ctx.lat_head;
 #ifdef WFST_PHASE_TIMING
     if (D.dbg) {
-      for (int k = 0; k < 8; ++k) atomicAdd(D.dbg + k, S.ph[k]);
-      for (int k = 8; k < 16; ++k) atomicAdd(D.dbg + 8 + 8000 + k, S.ph[k]);
+      for (int k = 0; k < 16; ++k) atomicAdd(D.dbg + k, S.ph[k]);
       unsigned long long tot = 0;
-      for (int k = 0; k < 5; ++k) tot += S.ph[k];
-      for (int k = 8; k < 16; ++k) tot += S.ph[k];
-      D.dbg[8 + blockIdx.x] = tot;                      // this lane's time for the call
-      if (blockIdx.x < 512) for (int k = 0; k < 16; ++k) D.dbg[8 + 8192 + blockIdx.x * 16 + k] = S.ph[k];
-      D.dbg[8 + 2048 + blockIdx.x] = S.dbg_tok;
-      D.dbg[8 + 4096 + blockIdx.x] = S.dbg_iters;
-      D.dbg[8 + 6144 + blockIdx.x] = S.dbg_arcs;
+      for (int k = 0; k < 16; ++k) if (k != 5 && k != 6 && k != 7 && k != 13) tot += S.ph[k];
+      D.dbg[16 + blockIdx.x] = tot;                     // this lane's time for the call
+      D.dbg[16 + 2048 + blockIdx.x] = S.dbg_tok;
+      D.dbg[16 + 4096 + blockIdx.x] = S.dbg_arcs;
     }
 #endif
   }

@@ -64,7 +64,7 @@ def test_random_call_patterns(seed):
     # with blocks the ring only has to hold what a channel produces between two seals; without, everything
     dec = B.WfstDecoder(B.WfstGraph(g), beam, lbeam, alpha, num_channels=n_ch, max_lanes=n_ch, max_frames=max(lens),
                         token_capacity=4096, lattice_capacity=most, snapshot_blocks=n_blocks, snapshot_block_capacity=most * n_ch,
-                        lane_threads=int(rng.choice([0, 512, 1024])))
+                        lane_threads=int(rng.choice([0, 256, 512, 1024])), frame_form=int(rng.integers(0, 4) == 0))
     dec.init_channels(list(range(n_ch)))
     dev = [torch.from_numpy(r).cuda() for r in rows]
     fed = [0] * n_ch                              # frames given to each channel so far
@@ -140,7 +140,7 @@ def test_random_heavy_frames(seed):
     od = oracle.OracleDecoder(oracle.OracleGraph(g), beam, lbeam, alpha)
     od.advance(rows)
     dec = B.WfstDecoder(B.WfstGraph(g), beam, lbeam, alpha, num_channels=1, max_lanes=1, max_frames=T, token_capacity=1 << 16,
-                        lattice_capacity=len(od.lattice()[0]) + 16, lane_threads=int(rng.choice([512, 1024])))
+                        lattice_capacity=len(od.lattice()[0]) + 16, lane_threads=int(rng.choice([256, 512, 1024])))
     dec.init_channels([0])
     t = torch.from_numpy(rows).cuda()
     pos = 0
