@@ -24,6 +24,7 @@
 // A frame that outgrows the LDS structures, or meets a state whose out-degrees do not fit the
 // degree info, is redone by the general frame; nothing has been committed at that point.
 #pragma once
+#include <type_traits>
 #include "wfst_lane.h"
 
 namespace wfst {
@@ -31,7 +32,7 @@ namespace wfst {
 // Returns false if the frame must be redone by the general frame.
 template <int NT>
 __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, const float *ll, const float *ll_next,
-                            bool is_init, Aux *aux, uint32_t *dkey, uint32_t *dslot, long long *foff, HTok *hist, LatInt *lat) {
+                            bool is_init, int chan) {
   using L = LightCfg<NT>;
   constexpr int NW = NT / 64, U = L::EXP_U;
   constexpr uint32_t mask = L::SLOTS - 1;
@@ -46,6 +47,11 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
   const long long out_base = ctx.hist_used;
   const int n_in = is_init ? 0 : ctx.n_in;
   const int info_shift = D.g.info_shift;
+  const uint32_t sink = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float *)S.sink;
+  // (the lane's buffers are addressed from the decoder's arrays where they are used: eight
+  // pointers less to keep in registers across the whole kernel)
+  HTok *const hist = D.hist + (size_t)chan * (size_t)D.hist_cap;
+  LatInt *const lat = D.lat + (size_t)chan * (size_t)D.lat_cap;
   const uint32_t claim_limit = min((uint32_t)L::CLAIM_LIMIT, (uint32_t)D.tokcap);
 
   // ---- 0. what the previous light frame left: its table entries are cleared here, beside the
@@ -99,12 +105,15 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
         uint32_t b0[3], b1[3] = {0, 0, 0};       // the first two arcs' loads in flight together
         b0[0] = a0[0]; b0[1] = a0[1]; b0[2] = a0[2];
         if (np > 1) { b1[0] = a0[3]; b1[1] = a0[4]; b1[2] = a0[5]; }
-        S.enote[e0] = ENote{__uint_as_float(b0[1]), r0, b0[0], ((info_shift ? (b0[2] >> 16) : INFO_UNKNOWN) << 16) | 0xFFFFu};
-        if (np > 1) S.enote[e0 + 1] = ENote{__uint_as_float(b1[1]), r0 + 1, b1[0], ((info_shift ? (b1[2] >> 16) : INFO_UNKNOWN) << 16) | 0xFFFFu};
+        auto park = [&](uint32_t e, uint32_t rr, uint32_t c0, uint32_t c1, uint32_t c2) {
+          S.enote[e] = ENote{__uint_as_float(c1), rr, c0, ((info_shift ? (c2 >> 16) : INFO_UNKNOWN) << 16) | 0xFFFFu};
+        };
+        park(e0, r0, b0[0], b0[1], b0[2]);
+        if (np > 1) park(e0 + 1, r0 + 1, b1[0], b1[1], b1[2]);
         for (uint32_t k = 2; k < np; ++k) {
           const uint32_t *a = a0 + 3 * (size_t)k;
           const uint32_t c0 = a[0], c1 = a[1], c2 = a[2];
-          S.enote[e0 + k] = ENote{__uint_as_float(c1), r0 + k, c0, ((info_shift ? (c2 >> 16) : INFO_UNKNOWN) << 16) | 0xFFFFu};
+          park(e0 + k, r0 + k, c0, c1, c2);
         }
       }
     }
@@ -140,53 +149,89 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
       int wb[NW];                              // arcs before each wave of the tile
       int total = 0;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) { wb[w] = total; total += S.wtot[w]; }
+      for (int w = 0; w < NW; ++w) { wb[w] = total; total += uni(S.wtot[w]); }
       emit_arcs += (unsigned long long)total;
       if (tb == 0) simple = n_in <= NT && total <= NT * U;
       for (int j0 = 0; j0 < total; j0 += NT * U) {
-        uint32_t dw[U], kx[U], w2[U]; float cw[U];
+        uint32_t dw[U], kx[U], w2[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const int j = j0 + u * NT + tid;
-          kx[u] = KEY_NONE; dw[u] = 0; w2[u] = 0; cw[u] = 0.f; nslot[u] = NOSLOT;
-          if (j < total) {
+        for (int u = 0; u < U; ++u) { kx[u] = KEY_NONE; dw[u] = 0; w2[u] = 0; nslot[u] = NOSLOT; }
+        uint32_t m = KEY_NONE;
+        bool bad = false;
+        // Arc j0 + u * NT + tid is this thread's u-th arc of the round.  A wave runs only as many
+        // of the U slots as it has arcs for (the same number for all its lanes), and runs them
+        // side by side: the steps of the searches, then all record loads, then all score loads.
+        auto expand = [&](auto ua_const) {
+          constexpr int UA = decltype(ua_const)::value;
+          uint32_t wt[UA]; float ct[UA], sc_ll[UA];
+          int jj[UA], lo[UA], hi[UA], wv[UA];
+#pragma unroll
+          for (int u = 0; u < UA; ++u) {
+            // (a lane past the end re-reads the last arc, so that no load is conditional)
+            const int j = min(j0 + u * NT + tid, total - 1);
             int w = 0;                         // the wave whose tokens own arc j, then the token inside it
 #pragma unroll
             for (int q = 1; q < NW; ++q) w += (j >= wb[q]) ? 1 : 0;
             int base = 0;
 #pragma unroll
             for (int q = 1; q < NW; ++q) base = (w == q) ? wb[q] : base;
-            const int jj = j - base;
-            const int *sc = S.scan + w * 64;
-            int lo = 0, hi = 63;               // largest k with sc[k] <= jj
+            jj[u] = j - base; wv[u] = w * 64; lo[u] = 0; hi[u] = 63;
+          }
 #pragma unroll
-            for (int it = 0; it < 6; ++it) { const int mid = (lo + hi + 1) >> 1; if (sc[mid] <= jj) lo = mid; else hi = mid - 1; }
-            const int k = w * 64 + lo;
-            kk[u] = tb + k;
-            r[u] = (S.tok_h[tb + k] & HMASK) + 1u + (uint32_t)(jj - sc[lo]);
+          for (int it = 0; it < 6; ++it) {     // largest k with scan[k] <= jj
+            int v[UA];
+#pragma unroll
+            for (int u = 0; u < UA; ++u) v[u] = S.scan[wv[u] + ((lo[u] + hi[u] + 1) >> 1)];
+#pragma unroll
+            for (int u = 0; u < UA; ++u) { const int mid = (lo[u] + hi[u] + 1) >> 1; if (v[u] <= jj[u]) lo[u] = mid; else hi[u] = mid - 1; }
+          }
+#pragma unroll
+          for (int u = 0; u < UA; ++u) {
+            const int k = tb + wv[u] + lo[u];
+            kk[u] = k;
+            r[u] = (S.tok_h[k] & HMASK) + 1u + (uint32_t)(jj[u] - S.scan[wv[u] + lo[u]]);
+            ct[u] = S.tok_c[k];
+          }
+#pragma unroll
+          for (int u = 0; u < UA; ++u) {
             const uint32_t *a = rec + 3 * (size_t)r[u];
-            dw[u] = a[0];
-            cw[u] = S.tok_c[tb + k] + __uint_as_float(a[1]);
-            w2[u] = a[2];
-            kx[u] = 0;                         // marks the candidate as present until its cost is known
+            dw[u] = a[0]; wt[u] = a[1]; w2[u] = a[2];
           }
-        }
-        uint32_t m = KEY_NONE;
+          __builtin_amdgcn_sched_barrier(0);   // (keeps the loads above together and their uses below them)
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          if (kx[u] != KEY_NONE) {
-            x[u] = cw[u] - ll[w2[u] & D.g.pdf_mask];
-            if (x[u] != x[u] || x[u] == -INFINITY) { atomicOr(&C.flags, F_NAN); kx[u] = KEY_NONE; }
-            else { kx[u] = okey(x[u]); m = min(m, kx[u]); }
+          for (int u = 0; u < UA; ++u) sc_ll[u] = ll[w2[u] & D.g.pdf_mask];
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int u = 0; u < UA; ++u) {
+            x[u] = (ct[u] + __uint_as_float(wt[u])) - sc_ll[u];
+            const bool have = j0 + u * NT + tid < total;
+            const bool nan = x[u] != x[u] || x[u] == -INFINITY;
+            bad |= have && nan;
+            kx[u] = (have && !nan) ? okey(x[u]) : KEY_NONE;
+            m = min(m, kx[u]);
           }
+        };
+        const int left = total - j0 - uni(wid) * 64;        // arcs of the round from this wave's first lane on
+        const int ua = left <= 0 ? 0 : min(U, (left + NT - 1) / NT);
+        static_assert(U == 4 || U == 8, "slots per thread");
+        switch (ua) {
+          case 0: break;
+          case 1: expand(std::integral_constant<int, 1>{}); break;
+          case 2: expand(std::integral_constant<int, 2>{}); break;
+          case 3: expand(std::integral_constant<int, 3>{}); break;
+          case 4: expand(std::integral_constant<int, 4>{}); break;
+          default:
+            if constexpr (U > 4) expand(std::integral_constant<int, U>{});
+            break;
         }
+        if (bad) atomicOr(&C.flags, F_NAN);
         m = wave_min_u32(m);
         if (lane == 0 && m != KEY_NONE) atomicMin(&C.best, m);
         lds_barrier();
         PHASE_MARK(2);
         // within (best so far + beam): with one round that is the frame's final cutoff, with
         // more rounds a bound that is never below it (entries above the final one are ignored later)
-        const float cut = key2f(C.best) + D.beam;
+        const float cut = key2f(uni(C.best)) + D.beam;
         const bool stop = (C.flags & F_NAN) != 0 || (C.cnt[0] & CNT_RESTART) != 0;   // (only saves work: the frame is given up later)
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -199,7 +244,7 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
           else if (D.lattice_on || im) {
             const uint32_t ai = wave_alloc(&C.auxn);
             if (ai >= (uint32_t)D.auxcap) atomicOr(&C.flags, F_LATOVF);
-            else aux[ai] = Aux{(uint32_t)sl, x[u], r[u], (uint32_t)kk[u]};
+            else (D.aux + (size_t)blockIdx.x * (size_t)D.auxcap)[ai] = Aux{(uint32_t)sl, x[u], r[u], (uint32_t)kk[u]};
           }
         }
       }
@@ -212,11 +257,11 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
 
   // (from here on the frame's flags and its first counter are stable: closure rounds report
   // through their own counters)
-  const uint32_t bestk = C.best;
-  const unsigned long long c0 = C.cnt[0];
+  const uint32_t bestk = uni(C.best);
+  const unsigned long long c0 = uni(C.cnt[0]);
   int abort_code = 0;                          // 1: give the frame to the general form
   {
-    const uint32_t fl = C.flags;
+    const uint32_t fl = uni(C.flags);
     if (c0 & CNT_RESTART) abort_code = 1;
     else if (fl & F_NAN) abort_code = E_NAN_INPUT;
     else if (fl & F_LATOVF) abort_code = E_LATTICE_OVERFLOW;
@@ -253,7 +298,7 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
         }
       }
       lds_barrier();
-      const unsigned long long cv = *ctr;        // stable: the next round appends to another counter
+      const unsigned long long cv = uni(*ctr);   // stable: the next round appends to another counter
       w0 = w1; w1 = min(w1 + ((uint32_t)cv & CNT_ENTRIES), (uint32_t)L::QCAP); nclaim += (uint32_t)(cv >> 32);
       ++iters;
       if (cv & CNT_RESTART) { abort_code = 1; break; }
@@ -273,11 +318,10 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
   const uint32_t n_q = w1;
 
   PHASE_MARK(4);
-  // touch the next frame's row of scores (one 64-byte line per load): nothing below waits for
-  // these loads, and by the next expansion its gathers by pdf id hit L2
-  float touch = 0.f;
+  // fetch ahead the next frame's row of scores (one 64-byte line per load): by the next
+  // expansion its gathers by pdf id hit L2
   if (ll_next)
-    for (int p = tid * 16; p < D.g.num_pdfs; p += NT * 16) touch += ll_next[p];
+    for (int p = tid * 16; p < D.g.num_pdfs; p += NT * 16) fetch_ahead(ll_next + p, sink);
 
   // ---- 3 + 4. max-active selection and contraction ------------------------------------------
   // A kept token gets its index in the new frame (low bits of its slot's aux) and its entry in
@@ -303,6 +347,8 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
         slots[sl].aux = (sv.aux & ~POS_MASK) | pos;
       }
     } else {
+      uint32_t *const dkey = D.dkey + (size_t)blockIdx.x * (size_t)D.tokcap;
+      uint32_t *const dslot = D.dslot + (size_t)blockIdx.x * (size_t)D.tokcap;
       for (uint32_t i = tid; i < n_q; i += NT) {
         const uint32_t e = S.lq[i];
         if (e & LQ_DUP) continue;
@@ -316,11 +362,11 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
         atomicMin(&C.kmin, key); atomicMax(&C.kmax, key);
       }
       __syncthreads();
-      const int n = (int)C.nvalid;
+      const int n = (int)uni(C.nvalid);
       uint32_t theta = KEY_NONE, h_theta = 0xFFFFFFFFu;       // keep key < theta, or == theta with handle <= h_theta
       if (n > D.max_active) {
         uint32_t n_less, n_eq;
-        block_select<NT>(S, n, (uint32_t)D.max_active, C.kmin, C.kmax,
+        block_select<NT>(S, n, (uint32_t)D.max_active, uni(C.kmin), uni(C.kmax),
                          [&](int i, uint32_t &v) { v = dkey[i]; return true; }, theta, n_less, n_eq);
         const uint32_t need_eq = (uint32_t)D.max_active - n_less;
         if (need_eq < n_eq) {
@@ -353,8 +399,9 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
   if (lane == 0 && eps_cnt) atomicAdd(&C.eps_arcs, eps_cnt);
   lds_barrier();
   PHASE_MARK(8);
-  const uint32_t n_out = (abort_code == 0) ? min(C.nout, (uint32_t)D.max_active) : 0u;
-  const uint32_t n_valid = (abort_code == 0) ? max(C.nvalid, C.nout) : 0u;
+  const uint32_t nout_all = uni(C.nout);
+  const uint32_t n_out = (abort_code == 0) ? min(nout_all, (uint32_t)D.max_active) : 0u;
+  const uint32_t n_valid = (abort_code == 0) ? max(uni(C.nvalid), nout_all) : 0u;
 
   // ---- 5. history records, back-pointers and lattice records ---------------------------------
   // Every candidate arc is looked at once more, with final costs.  The one equal to the table's
@@ -388,7 +435,8 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
       for (int u = 0; u < U; ++u)
         if (nslot[u] != NOSLOT) emitting_note(nslot[u], x[u], r[u], (uint32_t)kk[u]);
     } else {
-      const uint32_t n_aux = min(C.auxn, (uint32_t)D.auxcap);
+      const Aux *const aux = D.aux + (size_t)blockIdx.x * (size_t)D.auxcap;
+      const uint32_t n_aux = min(uni(C.auxn), (uint32_t)D.auxcap);
       for (uint32_t i0 = 0; i0 < n_aux; i0 += NT * LAT_U) {
         Aux a[LAT_U];
 #pragma unroll
@@ -436,20 +484,19 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
     }
   }
   lds_barrier();
-  asm volatile("" ::"v"(touch));
   PHASE_MARK(9);
 
   // ---- 6. the lane's state after the frame (every thread computes the same values) -----------
-  if (abort_code == 0 && (C.flags & F_LATOVF)) abort_code = E_LATTICE_OVERFLOW;
-  const long long lat_new = min((long long)C.latn, ctx.lat_room);
-  if (tid == 0) foff[nf + 1] = out_base + n_out;
+  if (abort_code == 0 && (uni(C.flags) & F_LATOVF)) abort_code = E_LATTICE_OVERFLOW;
+  const long long lat_new = min((long long)uni(C.latn), ctx.lat_room);
+  if (tid == 0) (D.frame_off + (size_t)chan * (size_t)(D.max_frames + 2))[nf + 1] = out_base + n_out;
   ctx.nf = nf + 1;
   ctx.in_off = out_base; ctx.n_in = (int)n_out;
   ctx.hist_used = out_base + n_out;
   ctx.lat_total += lat_new; ctx.lat_room -= lat_new;
   ctx.lat_pos += lat_new;
   if (ctx.lat_pos >= D.lat_cap) ctx.lat_pos -= D.lat_cap;
-  ctx.arcs_expanded += (long long)(emit_arcs + (unsigned long long)C.eps_arcs);
+  ctx.arcs_expanded += (long long)(emit_arcs + (unsigned long long)uni(C.eps_arcs));
   ctx.max_pre = max(ctx.max_pre, (int)n_valid);
   ctx.max_post = max(ctx.max_post, (int)n_out);
   ctx.iters_max = max(ctx.iters_max, iters);

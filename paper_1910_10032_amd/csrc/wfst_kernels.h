@@ -42,15 +42,11 @@ template <int NT>
 __global__ void __launch_bounds__(NT, NT >= 512 ? 4 : 2) k_advance(DecDev D, const LaneParam *__restrict__ lanes, int is_init) {
   __shared__ LaneShared<NT> S;
   const int tid = threadIdx.x;
-  const LaneParam lp = lanes[blockIdx.x];
+  LaneParam lp = lanes[blockIdx.x];
+  lp.ll = (const float *)uni((unsigned long long)lp.ll); lp.chan = uni(lp.chan); lp.n_frames = uni(lp.n_frames); lp.stride = uni(lp.stride);
+  lp.snap_every = uni(lp.snap_every); lp.snap_id0 = uni(lp.snap_id0); lp.n_snaps = uni(lp.n_snaps);
   ChanState *cs = D.chan + lp.chan;
-  Slot *slots = D.slots + (size_t)blockIdx.x * D.H;
-  uint32_t *queue = D.queue + (size_t)blockIdx.x * (size_t)D.qcap;
-  Aux *aux = D.aux + (size_t)blockIdx.x * (size_t)D.auxcap;
-  uint32_t *dkey = D.dkey + (size_t)blockIdx.x * (size_t)D.tokcap;
-  uint32_t *dslot = D.dslot + (size_t)blockIdx.x * (size_t)D.tokcap;
   long long *foff = D.frame_off + (size_t)lp.chan * (size_t)(D.max_frames + 2);
-  HTok *hist = D.hist + (size_t)lp.chan * (size_t)D.hist_cap;
   LatInt *lat = D.lat + (size_t)lp.chan * (size_t)D.lat_cap;
 
   const Slot fresh{~0ull, EMPTY, 0xFFFFFFFFu};
@@ -61,24 +57,29 @@ __global__ void __launch_bounds__(NT, NT >= 512 ? 4 : 2) k_advance(DecDev D, con
 #ifdef WFST_PHASE_TIMING
     for (int k = 0; k < 16; ++k) S.ph[k] = 0;
     S.dbg_tok = 0; S.dbg_iters = 0; S.dbg_arcs = 0;
-    S.tlast = wall_clock64();
 #endif
   }
   LaneCtx ctx;
+#ifdef WFST_PHASE_TIMING
+  ctx.tlast = wall_clock64();
+#endif
   if (is_init) {
     ctx.status = 0; ctx.nf = 0; ctx.hist_used = 0; ctx.lat_room = D.lat_cap; ctx.lat_pos = 0; ctx.lat_total = 0;
     ctx.arcs_expanded = 0; ctx.lat_head = 0; ctx.lat_head_pos = 0; ctx.max_pre = 0; ctx.max_post = 0; ctx.iters_max = 0;
   } else {
-    ctx.status = cs->status; ctx.nf = cs->num_frames; ctx.hist_used = cs->hist_used;
-    ctx.lat_head = cs->lat_head; ctx.lat_total = cs->lat_total;
+    ctx.status = uni(cs->status); ctx.nf = uni(cs->num_frames); ctx.hist_used = uni(cs->hist_used);
+    ctx.lat_head = uni(cs->lat_head); ctx.lat_total = uni(cs->lat_total);
     ctx.lat_room = D.lat_cap - (ctx.lat_total - ctx.lat_head);
     ctx.lat_pos = ctx.lat_total % D.lat_cap;
     ctx.lat_head_pos = ctx.lat_head % D.lat_cap;
-    ctx.arcs_expanded = cs->arcs_expanded; ctx.max_pre = cs->max_pre;
-    ctx.max_post = cs->max_post; ctx.iters_max = cs->closure_iters_max;
+    ctx.arcs_expanded = uni(cs->arcs_expanded); ctx.max_pre = uni(cs->max_pre);
+    ctx.max_post = uni(cs->max_post); ctx.iters_max = uni(cs->closure_iters_max);
   }
   ctx.in_off = 0; ctx.n_in = 0;
-  if (!is_init && ctx.nf >= 1 && ctx.nf <= D.max_frames + 1) { ctx.in_off = foff[ctx.nf - 1]; ctx.n_in = (int)(foff[ctx.nf] - foff[ctx.nf - 1]); }
+  if (!is_init && ctx.nf >= 1 && ctx.nf <= D.max_frames + 1) {
+    const long long o0 = uni(foff[ctx.nf - 1]), o1 = uni(foff[ctx.nf]);
+    ctx.in_off = o0; ctx.n_in = (int)(o1 - o0);
+  }
   ctx.pending_clear = 0; ctx.par = 0; ctx.tok_valid = false;
   __syncthreads();
   // Seal the lane's state as the next snapshot of this call.  With snapshot blocks the lattice
@@ -107,7 +108,7 @@ __global__ void __launch_bounds__(NT, NT >= 512 ? 4 : 2) k_advance(DecDev D, con
         S.blk_pos = pos;
       }
       __syncthreads();
-      const long long pos = S.blk_pos;
+      const long long pos = uni(S.blk_pos);
       if (pos < 0 && ctx.status == 0) ctx.status = E_LATTICE_OVERFLOW;
       if (pos >= 0) {
         LatRec *out = D.blk_recs + (size_t)slot * (size_t)D.blk_cap + (size_t)pos;
@@ -135,10 +136,12 @@ __global__ void __launch_bounds__(NT, NT >= 512 ? 4 : 2) k_advance(DecDev D, con
       }
       ctx.lat_head = ctx.lat_total; ctx.lat_head_pos = ctx.lat_pos; ctx.lat_room = D.lat_cap;
     }
-    // every thread's stores (tokens, lattice records, the block) must have reached device
-    // memory before the snapshot is published: each thread releases its own, then the barrier,
-    // then thread 0 publishes with a system-scope release
-    __threadfence();
+    // Every thread's stores (tokens, lattice records, the block) must have reached the L2 before
+    // thread 0 publishes: each wave waits until its own stores have been acknowledged, then the
+    // barrier, then thread 0's system-scope release, which writes the L2's dirty lines back.
+    // (One release per lane and snapshot: a device-scope fence in every thread would flush and
+    // invalidate the cache eight times over and slows all lanes of the chip down noticeably.)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (tid == 0) {
       ChanSnap *sp = D.snap + (size_t)lp.chan * SNAP_RING + (size_t)(id % SNAP_RING);
@@ -157,10 +160,12 @@ __global__ void __launch_bounds__(NT, NT >= 512 ? 4 : 2) k_advance(DecDev D, con
       S.lat_total = ctx.lat_total; S.lat_pos = ctx.lat_pos; S.arcs_expanded = ctx.arcs_expanded;
     }
     __syncthreads();                                  // (also: the light frames' history stores have arrived)
-    general_frame<NT>(D, S, ll, is_init != 0, slots, queue, aux, dkey, dslot, foff, hist, lat);
-    ctx.status = S.status; ctx.nf = S.nf; ctx.n_in = S.n_in; ctx.max_pre = S.max_pre; ctx.max_post = S.max_post;
-    ctx.iters_max = S.iters_max; ctx.in_off = S.in_off; ctx.hist_used = S.hist_used; ctx.lat_room = S.lat_room;
-    ctx.lat_total = S.lat_total; ctx.lat_pos = S.lat_pos; ctx.arcs_expanded = S.arcs_expanded;
+    general_frame<NT>(D, S, ll, is_init != 0, D.slots + (size_t)blockIdx.x * D.H, D.queue + (size_t)blockIdx.x * (size_t)D.qcap,
+                      D.aux + (size_t)blockIdx.x * (size_t)D.auxcap, D.dkey + (size_t)blockIdx.x * (size_t)D.tokcap,
+                      D.dslot + (size_t)blockIdx.x * (size_t)D.tokcap, foff, D.hist + (size_t)lp.chan * (size_t)D.hist_cap, lat);
+    ctx.status = uni(S.status); ctx.nf = uni(S.nf); ctx.n_in = uni(S.n_in); ctx.max_pre = uni(S.max_pre); ctx.max_post = uni(S.max_post);
+    ctx.iters_max = uni(S.iters_max); ctx.in_off = uni(S.in_off); ctx.hist_used = uni(S.hist_used); ctx.lat_room = uni(S.lat_room);
+    ctx.lat_total = uni(S.lat_total); ctx.lat_pos = uni(S.lat_pos); ctx.arcs_expanded = uni(S.arcs_expanded);
     ctx.tok_valid = false;
     __syncthreads();                                  // all have read the state before the next general frame rewrites it
   };
@@ -175,7 +180,7 @@ __global__ void __launch_bounds__(NT, NT >= 512 ? 4 : 2) k_advance(DecDev D, con
       const float *ll_next = (!is_init && f + 1 < nframes) ? ll + lp.stride : nullptr;
       bool done = false;
       if (light_ok && (is_init || ctx.n_in <= LightCfg<NT>::NIN_MAX))
-        done = light_frame<NT>(D, S, ctx, ll, ll_next, is_init != 0, aux, dkey, dslot, foff, hist, lat);
+        done = light_frame<NT>(D, S, ctx, ll, ll_next, is_init != 0, lp.chan);
       if (!done) {
 #ifdef WFST_PHASE_TIMING
         if (tid == 0) S.ph[6] += 1;
@@ -211,6 +216,8 @@ __global__ void __launch_bounds__(NT, NT >= 512 ? 4 : 2) k_advance(DecDev D, con
       D.dbg[16 + blockIdx.x] = tot;                     // this lane's time for the call
       D.dbg[16 + 2048 + blockIdx.x] = S.dbg_tok;
       D.dbg[16 + 4096 + blockIdx.x] = S.dbg_arcs;
+      D.dbg[16 + 6144 + blockIdx.x] = S.ph[6];            // frames in the general form
+      D.dbg[16 + 8192 + blockIdx.x] = S.ph[11];           // time in them
     }
 #endif
   }

@@ -41,6 +41,16 @@ __device__ __forceinline__ uint32_t wave_alloc(uint32_t *counter) {
   base = (uint32_t)__builtin_amdgcn_readlane((int)base, leader);
   return base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
 }
+// Fetch ahead: start the load of the line that holds *p without waiting for it and without
+// tying up a register - the value is delivered to a scratch word in LDS (`sink`: the LDS
+// address of 64 floats nobody reads) by the LDS-direct form of the load.  A later ordinary
+// load of the same line finds it in the cache or on its way.  The compiler does not count this
+// load in its vmcnt bookkeeping; since vector memory operations complete in order, the waits
+// it inserts for its own loads stay correct (an older operation in the queue can only make
+// them wait for slightly more than they need).
+__device__ __forceinline__ void fetch_ahead(const void *p, uint32_t sink) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(p), "s"(sink) : "m0", "memory");
+}
 __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
@@ -102,7 +112,20 @@ struct LaneCtx {
   uint32_t pending_clear;    // queue entries of the last light frame whose table slots are still to be cleared
   int par;                   // counter set the next light frame uses
   bool tok_valid;            // the LDS token list holds the frame the next one starts from
+#ifdef WFST_PHASE_TIMING
+  unsigned long long tlast;
+#endif
 };
+// A value every lane of the wavefront holds alike, moved to a scalar register (values that
+// come from LDS or from vector loads sit in vector registers otherwise, and so would
+// everything computed from them: the lane's whole state and its arithmetic).
+__device__ __forceinline__ uint32_t uni(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ unsigned long long uni(unsigned long long v) {
+  return ((unsigned long long)uni((uint32_t)(v >> 32)) << 32) | uni((uint32_t)v);
+}
+__device__ __forceinline__ long long uni(long long v) { return (long long)uni((unsigned long long)v); }
+__device__ __forceinline__ float uni(float v) { return __uint_as_float(uni(__float_as_uint(v))); }
 
 
 
@@ -192,6 +215,7 @@ template <int NT>
 struct LaneShared {
   int wave_tmp[NT / 64];
   int wtot[NT / 64];
+  float sink[64];              // where fetch_ahead delivers; never read
   union {                      // the expansion's tile arrays and the selection's histogram never coexist
     struct { int scan[NT]; float cost[NT]; uint32_t base[NT]; };
     uint32_t hist[NBINS];
@@ -209,7 +233,7 @@ struct LaneShared {
   long long lat_pos;           // ring position of record number lat_total
   long long blk_pos;           // seal scratch
 #ifdef WFST_PHASE_TIMING
-  unsigned long long ph[16], tlast, dbg_tok, dbg_iters, dbg_arcs;
+  unsigned long long ph[16], dbg_tok, dbg_iters, dbg_arcs;
 #endif
   // -- light frame
   FrameCtr fc[2];
@@ -222,7 +246,8 @@ struct LaneShared {
 };
 
 #ifdef WFST_PHASE_TIMING
-#define PHASE_MARK(k) do { if (threadIdx.x == 0) { unsigned long long t_ = wall_clock64(); S.ph[k] += t_ - S.tlast; S.tlast = t_; } } while (0)
+// (instrumented builds) thread 0 adds the time since its previous mark to phase k
+#define PHASE_MARK(k) do { if (threadIdx.x == 0) { unsigned long long t_ = wall_clock64(); atomicAdd(&S.ph[k], t_ - ctx.tlast); ctx.tlast = t_; } } while (0)
 #else
 #define PHASE_MARK(k) do { } while (0)
 #endif
