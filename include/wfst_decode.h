@@ -56,7 +56,9 @@ enum {
   WFST_E_NAN_INPUT = -9,        /* a score read by the channel was NaN or +inf                */
   WFST_E_BROKEN_TRACE = -10,    /* a best incoming arc starts at a state that holds no token  */
   WFST_E_DEVICE = -11,          /* HIP runtime error (allocation, launch, copy)               */
-  WFST_E_HISTORY_OVERFLOW = -12 /* token history of the channel or max_frames exhausted       */
+  WFST_E_HISTORY_OVERFLOW = -12,/* token history of the channel or max_frames exhausted       */
+  WFST_E_SCRATCH_LIMIT = -13    /* wfst_decode_final_lattice_noalloc: the channel needs more
+                                   than the entry point's fixed scratch                       */
 };
 
 typedef struct wfst_graph wfst_graph_t;     /* opaque; device-resident, immutable            */
@@ -275,6 +277,23 @@ typedef struct {
 int wfst_decode_final_lattice(wfst_decoder_t *decoder, int32_t channel, int32_t use_final,
                               wfst_lat_arc_t *out, int64_t cap, int64_t *n, int32_t out_is_device,
                               wfst_lattice_info_t *info);
+
+/* wfst_decode_final_lattice for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same result, but the
+ * pass's scratch - one 32-bit word per kept token of the channel, one 64-bit offset per frame
+ * and a small result block - lives in a fixed 8 MiB array inside the library's device image
+ * instead of being allocated per call, and `out` must be DEVICE memory (no staging buffer).
+ * The call allocates nothing, on the device or through any allocating routine.  A channel that
+ * needs more scratch (4 * tokens kept + 8 * (frames + 3) + 64 bytes > 8 MiB, i.e. beyond about
+ * two million kept tokens) is rejected with WFST_E_SCRATCH_LIMIT and nothing is launched.  All
+ * calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two host
+ * threads, two decoders on different streams) race, so issue them one at a time; the array
+ * keeps the previous call's contents and every call initialises the part it uses.
+ * WFST_E_CAPACITY with *n = needed if cap is too small.  Synchronises with the decoder's
+ * stream. */
+int wfst_decode_final_lattice_noalloc(wfst_decoder_t *decoder, int32_t channel, int32_t use_final,
+                                      wfst_lat_arc_t *out, int64_t cap, int64_t *n,
+                                      wfst_lattice_info_t *info);
 
 /* Tokens kept for one frame of a channel (frame -1 = last), in no particular order.
  * out: HOST [cap].  A parity hook: the token history is what best_path walks. */

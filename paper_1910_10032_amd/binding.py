@@ -18,14 +18,14 @@ NO_ARC = 0xFFFFFFFF
 WFST_OK = 0
 WFST_E_INVALID_ARG, WFST_E_BAD_GRAPH, WFST_E_BAD_CHANNEL, WFST_E_NOT_INIT, WFST_E_CAPACITY = -1, -2, -3, -4, -5
 WFST_E_TOKEN_OVERFLOW, WFST_E_LATTICE_OVERFLOW, WFST_E_DEAD_CHANNEL, WFST_E_NAN_INPUT = -6, -7, -8, -9
-WFST_E_BROKEN_TRACE, WFST_E_DEVICE, WFST_E_HISTORY_OVERFLOW = -10, -11, -12
+WFST_E_BROKEN_TRACE, WFST_E_DEVICE, WFST_E_HISTORY_OVERFLOW, WFST_E_SCRATCH_LIMIT = -10, -11, -12, -13
 
 EXPORTS = [
     "wfst_decode_graph_load", "wfst_decode_graph_free", "wfst_decode_graph_bytes", "wfst_decode_create",
     "wfst_decode_destroy", "wfst_decode_state_bytes", "wfst_decode_init_channels", "wfst_decode_free_channels",
     "wfst_decode_advance", "wfst_decode_best_path_batch", "wfst_decode_best_path", "wfst_decode_best_path_arcs",
     "wfst_decode_lattice_arcs", "wfst_decode_lattice_arcs_batch", "wfst_decode_advance_snapshots",
-    "wfst_decode_snapshot_wait", "wfst_decode_snapshot_best_path_batch", "wfst_decode_snapshot_lattice_arcs", "wfst_decode_final_lattice", "wfst_decode_tokens", "wfst_decode_stats", "wfst_decode_set_profiling",
+    "wfst_decode_snapshot_wait", "wfst_decode_snapshot_best_path_batch", "wfst_decode_snapshot_lattice_arcs", "wfst_decode_final_lattice", "wfst_decode_final_lattice_noalloc", "wfst_decode_tokens", "wfst_decode_stats", "wfst_decode_set_profiling",
     "wfst_decode_profile", "wfst_decode_strerror",
 ]
 
@@ -92,6 +92,7 @@ def lib():
         L.wfst_decode_snapshot_best_path_batch.argtypes = [vp, i64, vp, i32, i32, vp, i32, vp, vp, vp, vp]
         L.wfst_decode_snapshot_lattice_arcs.argtypes = [vp, i64, vp, i32, vp, vp, vp, i64, i32, C.POINTER(i64), C.POINTER(vp)]
         L.wfst_decode_final_lattice.argtypes = [vp, i32, i32, vp, i64, C.POINTER(i64), i32, C.POINTER(wfst_lattice_info_t)]
+        L.wfst_decode_final_lattice_noalloc.argtypes = [vp, i32, i32, vp, i64, C.POINTER(i64), C.POINTER(wfst_lattice_info_t)]
         L.wfst_decode_tokens.argtypes = [vp, i32, i32, vp, i32, C.POINTER(i32)]
         L.wfst_decode_stats.argtypes = [vp, i32, C.POINTER(wfst_stats_t)]
         L.wfst_decode_set_profiling.argtypes = [vp, i32]
@@ -356,6 +357,17 @@ class WfstDecoder:
                 continue
             _check(rc, "wfst_decode_final_lattice")
             return out[:n.value].copy(), {k: getattr(info, k) for k, _ in wfst_lattice_info_t._fields_}
+
+    def final_lattice_device(self, channel: int, use_final: bool, out_ptr: int, cap: int, noalloc: bool = False):
+        """wfst_decode_final_lattice with DEVICE output (out_ptr: device address of cap records), or its
+        allocation-free variant: (number of kept arcs, info dict).  Raises WfstError (also for WFST_E_CAPACITY)."""
+        n, info = C.c_int64(), wfst_lattice_info_t()
+        if noalloc:
+            rc = lib().wfst_decode_final_lattice_noalloc(self.h, channel, int(use_final), out_ptr, cap, C.byref(n), C.byref(info))
+        else:
+            rc = lib().wfst_decode_final_lattice(self.h, channel, int(use_final), out_ptr, cap, C.byref(n), 1, C.byref(info))
+        _check(rc, "wfst_decode_final_lattice_noalloc" if noalloc else "wfst_decode_final_lattice")
+        return n.value, {k: getattr(info, k) for k, _ in wfst_lattice_info_t._fields_}
 
     def tokens(self, channel: int, frame: int = -1, cap: int = 1 << 14):
         while True:

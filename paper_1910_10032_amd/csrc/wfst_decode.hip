@@ -65,10 +65,34 @@ struct wfst_decoder {
   long long *d_ranges = nullptr;        // readout scratch [2 * max(num_channels, max_lanes) + 1]
   bool profiling = false;
   int num_cus = 0;                      // compute units of the device
+  void *noalloc_scratch = nullptr;      // this device's copy of `scratch`
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
 };
 
+// Scratch of the allocation-free entry point (wfst_decode_final_lattice_noalloc): a fixed
+// array in the library's device image.  Every GPU the library runs on holds its own copy at
+// its own address until the process ends; in host code the array's name is only a stand-in for
+// the symbol, so the address is looked up once per device and used from then on.
+constexpr size_t NOALLOC_SCRATCH_BYTES = (size_t)8 << 20;
+constexpr int MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+static void *g_scratch_ptr[MAX_DEVICES] = {};
+
 namespace {
+
+// Address of `scratch` on the current device (looked up on first use, with that device current).
+int scratch_address(void **out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return WFST_E_DEVICE; }
+  if (dev < 0 || dev >= MAX_DEVICES) return WFST_E_DEVICE;
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return WFST_E_DEVICE; }
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return 0;
+}
 
 template <class T> int dev_alloc(wfst_decoder *d, T **p, size_t n) {
   void *q = nullptr;
@@ -153,6 +177,7 @@ const char *wfst_decode_strerror(int code) {
     case WFST_E_BROKEN_TRACE: return "back-pointer chain is broken";
     case WFST_E_DEVICE: return "HIP runtime error";
     case WFST_E_HISTORY_OVERFLOW: return "token history or max_frames exceeded";
+    case WFST_E_SCRATCH_LIMIT: return "channel too large for the fixed scratch of the allocation-free entry point";
     default: return "unknown error";
   }
 }
@@ -279,6 +304,8 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
       (void)hipGetLastError(); delete d; return WFST_E_DEVICE;
     }
     d->num_cus = cus;
+    const int src = scratch_address(&d->noalloc_scratch);
+    if (src) { delete d; return src; }
   }
   DecDev &D = d->dev;
   D.g = graph->dev;
@@ -755,6 +782,36 @@ int wfst_decode_final_lattice(wfst_decoder_t *d, int32_t channel, int32_t use_fi
   if (li.status != 0) return li.status;
   if (!out_is_device && li.arcs_kept > 0)
     HIP_TRY(copy_sync(d, out, dst, sizeof(LatRec) * (size_t)li.arcs_kept, hipMemcpyDeviceToHost));
+  *n = li.arcs_kept;
+  info->arcs_in = li.arcs_in; info->arcs_kept = li.arcs_kept; info->frames = li.frames;
+  info->reached_final = li.reached_final; info->best_cost = li.best_cost;
+  info->density = (float)((double)li.arcs_kept / (double)std::max(li.frames - 1, 1));
+  return 0;
+}
+
+int wfst_decode_final_lattice_noalloc(wfst_decoder_t *d, int32_t channel, int32_t use_final, wfst_lat_arc_t *out, int64_t cap,
+                                      int64_t *n, wfst_lattice_info_t *info) {
+  if (!d || !n || !info || cap < 0 || (cap > 0 && !out)) return WFST_E_INVALID_ARG;
+  int rc = check_channels(d, &channel, 1, true);
+  if (rc) return rc;
+  ChanState cs;
+  rc = read_chan(d, channel, &cs);
+  if (rc) return rc;
+  if (cs.status != 0) return cs.status;
+  // the same scratch layout as wfst_decode_final_lattice, inside the fixed array
+  const size_t te_bytes = sizeof(uint32_t) * (size_t)std::max<long long>(cs.hist_used, 1);
+  const size_t rs_off = (te_bytes + 15) & ~(size_t)15;
+  const size_t info_off = rs_off + sizeof(long long) * ((size_t)cs.num_frames + 3);
+  const size_t need = info_off + sizeof(LatticeInfoDev);
+  if (need > NOALLOC_SCRATCH_BYTES) return WFST_E_SCRATCH_LIMIT;
+  char *base = (char *)d->noalloc_scratch;          // the looked-up device address, never the array's name
+  hipLaunchKernelGGL(k_final_lattice, dim3(1), dim3(1024), 0, d->last_stream, d->dev, channel, use_final, (uint32_t *)base,
+                     (long long *)(base + rs_off), (LatRec *)out, (long long)cap, (LatticeInfoDev *)(base + info_off));
+  HIP_TRY(hipGetLastError());
+  LatticeInfoDev li;
+  HIP_TRY(copy_sync(d, &li, base + info_off, sizeof(li), hipMemcpyDeviceToHost));
+  if (li.status == WFST_E_CAPACITY) { *n = li.arcs_kept; return WFST_E_CAPACITY; }
+  if (li.status != 0) return li.status;
   *n = li.arcs_kept;
   info->arcs_in = li.arcs_in; info->arcs_kept = li.arcs_kept; info->frames = li.frames;
   info->reached_final = li.reached_final; info->best_cost = li.best_cost;
