@@ -61,3 +61,39 @@ def check_final_lattice(dec, ch, od, label=""):
         assert np.float32(info["best_cost"]).view(np.uint32) == np.float32(want["best_cost"]).view(np.uint32), label
         assert bool(info["reached_final"]) == want["reached_final"], label
         assert info["frames"] == od.num_frames
+
+
+# ---- order-independent digests, for comparing every channel of a full-size workload ----------
+
+_M1, _M2, _G = np.uint64(0xBF58476D1CE4E5B9), np.uint64(0x94D049BB133111EB), np.uint64(0x9E3779B97F4A7C15)
+
+
+def _mix(x):
+    x = (x ^ (x >> np.uint64(30))) * _M1
+    x = (x ^ (x >> np.uint64(27))) * _M2
+    return x ^ (x >> np.uint64(31))
+
+
+def record_hashes(frame, arc, extra):
+    """One 64-bit hash per lattice record {frame, arc, extra cost bits}."""
+    with np.errstate(over="ignore"):
+        x = (frame.astype(np.uint64) << np.uint64(32)) | arc.astype(np.uint64)
+        x = _mix(x + _G)
+        return _mix(x ^ (np.ascontiguousarray(extra, np.float32).view(np.uint32).astype(np.uint64) * _G))
+
+
+def set_digest(hashes):
+    """(count, wrapping sum, xor) of a multiset of record hashes: equal multisets give equal digests,
+    whatever the order; different ones collide with negligible probability."""
+    with np.errstate(over="ignore"):
+        return (int(len(hashes)), int(hashes.sum(dtype=np.uint64)) if len(hashes) else 0,
+                int(np.bitwise_xor.reduce(hashes)) if len(hashes) else 0)
+
+
+def range_digests(hashes, starts, counts):
+    """set_digest of hashes[starts[i] : starts[i] + counts[i]] for every i, in one pass."""
+    with np.errstate(over="ignore"):
+        ps = np.concatenate([np.zeros(1, np.uint64), np.cumsum(hashes, dtype=np.uint64)])
+        px = np.concatenate([np.zeros(1, np.uint64), np.bitwise_xor.accumulate(hashes)]) if len(hashes) else np.zeros(1, np.uint64)
+        a, b = np.asarray(starts, np.int64), np.asarray(starts, np.int64) + np.asarray(counts, np.int64)
+        return np.asarray(counts, np.int64), ps[b] - ps[a], px[b] ^ px[a]
