@@ -309,6 +309,33 @@ int wfst_decode_stats(wfst_decoder_t *decoder, int32_t channel, wfst_stats_t *ou
 int wfst_decode_set_profiling(wfst_decoder_t *decoder, int32_t on);
 int wfst_decode_profile(wfst_decoder_t *decoder, int64_t *launches, double *total_ms);
 
+/* Channel-to-lane multiplexer (Section 3.1: the decoder keeps many channels and works on at
+ * most max_lanes of them per batch; host threads feed the lanes from the channels that have
+ * audio waiting, and switching a lane to another channel costs a few microseconds per batch).
+ * The multiplexer is a host-side queue over one decoder: chunks of scores are submitted per
+ * channel as they arrive, and every wfst_mux_step binds the channels that have waited longest
+ * (at most max_lanes, at most one chunk per channel and step) to the lanes of one
+ * wfst_decode_advance call.  A channel with further chunks queued goes to the back of the
+ * queue, so channels take turns.  Here a channel's state is addressed by its id and never
+ * copied, so the switch itself moves no data; what a step costs beyond the decoding is the
+ * host-side binding and the upload of the lanes' parameters.
+ *   wfst_mux_create   decoder: must outlive the multiplexer; its channels are initialised and
+ *                     read out by the caller through the decoder's own calls
+ *   wfst_mux_submit   loglikes: DEVICE rows [n_frames][stride] (n_frames >= 1), valid until the
+ *                     step that consumes them has completed on its stream
+ *   wfst_mux_step     issues one advance call on `stream` (NULL: default stream) for the waiting
+ *                     channels; *n_lanes = how many it bound (0: nothing was waiting, no call)
+ *   wfst_mux_pending  chunks submitted and not yet bound to a lane
+ *   wfst_mux_stats    batches issued and lanes bound so far
+ * Not thread-safe (one feeding thread per multiplexer). */
+typedef struct wfst_mux wfst_mux_t;
+int wfst_mux_create(wfst_decoder_t *decoder, wfst_mux_t **out);
+void wfst_mux_destroy(wfst_mux_t *mux);
+int wfst_mux_submit(wfst_mux_t *mux, int32_t channel, const float *loglikes, int32_t stride, int32_t n_frames);
+int wfst_mux_step(wfst_mux_t *mux, void *stream, int32_t *n_lanes);
+int64_t wfst_mux_pending(const wfst_mux_t *mux);
+int wfst_mux_stats(const wfst_mux_t *mux, int64_t *batches, int64_t *lanes_bound);
+
 const char *wfst_decode_strerror(int code);
 
 #ifdef __cplusplus

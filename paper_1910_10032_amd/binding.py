@@ -27,6 +27,7 @@ EXPORTS = [
     "wfst_decode_lattice_arcs", "wfst_decode_lattice_arcs_batch", "wfst_decode_advance_snapshots",
     "wfst_decode_snapshot_wait", "wfst_decode_snapshot_best_path_batch", "wfst_decode_snapshot_lattice_arcs", "wfst_decode_final_lattice", "wfst_decode_final_lattice_noalloc", "wfst_decode_tokens", "wfst_decode_stats", "wfst_decode_set_profiling",
     "wfst_decode_profile", "wfst_decode_strerror",
+    "wfst_mux_create", "wfst_mux_destroy", "wfst_mux_submit", "wfst_mux_step", "wfst_mux_pending", "wfst_mux_stats",
 ]
 
 
@@ -99,6 +100,14 @@ def lib():
         L.wfst_decode_profile.argtypes = [vp, C.POINTER(i64), C.POINTER(C.c_double)]
         L.wfst_decode_strerror.argtypes = [C.c_int]
         L.wfst_decode_strerror.restype = C.c_char_p
+        L.wfst_mux_create.argtypes = [vp, C.POINTER(vp)]
+        L.wfst_mux_destroy.argtypes = [vp]
+        L.wfst_mux_destroy.restype = None
+        L.wfst_mux_submit.argtypes = [vp, i32, vp, i32, i32]
+        L.wfst_mux_step.argtypes = [vp, vp, C.POINTER(i32)]
+        L.wfst_mux_pending.argtypes = [vp]
+        L.wfst_mux_pending.restype = i64
+        L.wfst_mux_stats.argtypes = [vp, C.POINTER(i64), C.POINTER(i64)]
         _lib = L
     return _lib
 
@@ -392,3 +401,40 @@ class WfstDecoder:
         n, ms = C.c_int64(), C.c_double()
         _check(lib().wfst_decode_profile(self.h, C.byref(n), C.byref(ms)), "wfst_decode_profile")
         return n.value, ms.value
+
+
+class WfstMux:
+    """wfst_mux_*: the channel-to-lane multiplexer over one decoder, one method per C entry point."""
+
+    def __init__(self, decoder: WfstDecoder):
+        self.decoder = decoder                      # keeps the decoder alive
+        self.h = C.c_void_p()
+        _check(lib().wfst_mux_create(decoder.h, C.byref(self.h)), "wfst_mux_create")
+
+    def destroy(self):
+        if self.h:
+            lib().wfst_mux_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def submit(self, channel: int, ptr: int, stride: int, n_frames: int) -> None:
+        """ptr: device address of the chunk's first row."""
+        _check(lib().wfst_mux_submit(self.h, channel, C.c_void_p(ptr), stride, n_frames), "wfst_mux_submit")
+
+    def step(self, stream: int = 0) -> int:
+        n = C.c_int32()
+        _check(lib().wfst_mux_step(self.h, C.c_void_p(stream), C.byref(n)), "wfst_mux_step")
+        return n.value
+
+    def pending(self) -> int:
+        return int(lib().wfst_mux_pending(self.h))
+
+    def stats(self):
+        a, b = C.c_int64(), C.c_int64()
+        _check(lib().wfst_mux_stats(self.h, C.byref(a), C.byref(b)), "wfst_mux_stats")
+        return a.value, b.value

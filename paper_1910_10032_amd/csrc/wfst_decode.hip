@@ -856,6 +856,85 @@ int wfst_decode_stats(wfst_decoder_t *d, int32_t channel, wfst_stats_t *out) {
   return 0;
 }
 
+// ---- channel-to-lane multiplexer (host side; Section 3.1) ---------------------------------------
+}  // extern "C"
+
+struct wfst_mux {
+  struct Chunk { const float *ll; int32_t stride, n_frames; };
+  wfst_decoder *dec = nullptr;
+  std::vector<std::deque<Chunk>> queued;   // per channel: chunks submitted, oldest first
+  std::deque<int32_t> waiting;             // channels with queued chunks, longest-waiting first; each at most once
+  std::vector<uint8_t> is_waiting;
+  std::vector<int32_t> lane_chan, lane_stride, lane_frames;   // the batch being bound
+  std::vector<const float *> lane_ll;
+  int64_t pending = 0, batches = 0, lanes_bound = 0;
+};
+
+extern "C" {
+
+int wfst_mux_create(wfst_decoder_t *d, wfst_mux_t **out) {
+  if (!d || !out) return WFST_E_INVALID_ARG;
+  wfst_mux *m = new (std::nothrow) wfst_mux;
+  if (!m) return WFST_E_DEVICE;
+  try {
+    m->dec = d;
+    m->queued.resize((size_t)d->cfg.num_channels);
+    m->is_waiting.assign((size_t)d->cfg.num_channels, 0);
+    const size_t nl = (size_t)d->cfg.max_lanes;
+    m->lane_chan.reserve(nl); m->lane_stride.reserve(nl); m->lane_frames.reserve(nl); m->lane_ll.reserve(nl);
+  } catch (const std::bad_alloc &) { delete m; return WFST_E_DEVICE; }
+  *out = m;
+  return 0;
+}
+
+void wfst_mux_destroy(wfst_mux_t *m) { delete m; }
+
+int wfst_mux_submit(wfst_mux_t *m, int32_t channel, const float *loglikes, int32_t stride, int32_t n_frames) {
+  if (!m || !loglikes || n_frames < 1) return WFST_E_INVALID_ARG;
+  wfst_decoder *d = m->dec;
+  if (channel < 0 || channel >= d->cfg.num_channels) return WFST_E_BAD_CHANNEL;
+  if (!d->inited[channel]) return WFST_E_NOT_INIT;
+  if (stride < d->dev.g.num_pdfs) return WFST_E_INVALID_ARG;
+  try {
+    m->queued[channel].push_back(wfst_mux::Chunk{loglikes, stride, n_frames});
+    if (!m->is_waiting[channel]) { m->waiting.push_back(channel); m->is_waiting[channel] = 1; }
+  } catch (const std::bad_alloc &) { return WFST_E_DEVICE; }
+  ++m->pending;
+  return 0;
+}
+
+int wfst_mux_step(wfst_mux_t *m, void *stream, int32_t *n_lanes) {
+  if (!m || !n_lanes) return WFST_E_INVALID_ARG;
+  wfst_decoder *d = m->dec;
+  m->lane_chan.clear(); m->lane_stride.clear(); m->lane_frames.clear(); m->lane_ll.clear();
+  // the channels that have waited longest get the lanes; one chunk each
+  const size_t first_round = m->waiting.size();
+  for (size_t seen = 0; seen < first_round && (int32_t)m->lane_chan.size() < d->cfg.max_lanes; ++seen) {
+    const int32_t c = m->waiting.front();
+    m->waiting.pop_front();
+    std::deque<wfst_mux::Chunk> &q = m->queued[c];
+    const wfst_mux::Chunk ck = q.front();
+    q.pop_front();
+    m->lane_chan.push_back(c); m->lane_ll.push_back(ck.ll); m->lane_stride.push_back(ck.stride); m->lane_frames.push_back(ck.n_frames);
+    if (!q.empty()) m->waiting.push_back(c);      // takes its next turn after the others
+    else m->is_waiting[c] = 0;
+  }
+  *n_lanes = (int32_t)m->lane_chan.size();
+  if (*n_lanes == 0) return 0;
+  m->pending -= *n_lanes;
+  ++m->batches; m->lanes_bound += *n_lanes;
+  return wfst_decode_advance(d, m->lane_chan.data(), *n_lanes, m->lane_ll.data(), m->lane_stride.data(), m->lane_frames.data(), stream);
+}
+
+int64_t wfst_mux_pending(const wfst_mux_t *m) { return m ? m->pending : 0; }
+
+int wfst_mux_stats(const wfst_mux_t *m, int64_t *batches, int64_t *lanes_bound) {
+  if (!m) return WFST_E_INVALID_ARG;
+  if (batches) *batches = m->batches;
+  if (lanes_bound) *lanes_bound = m->lanes_bound;
+  return 0;
+}
+
 #ifdef WFST_PHASE_TIMING
 // Instrumented builds only: summed per-phase wall-clock ticks (100 MHz) of workgroup leaders.
 int wfst_debug_phase_times(wfst_decoder_t *d, unsigned long long *out8, int reset) {

@@ -27,13 +27,13 @@ def build_host(force: bool = False) -> str:
 
 
 def build_device(force: bool = False) -> str:
-    """Compile the device log-likelihood generator for gfx950."""
-    src = os.path.join(_DIR, "loglikes.hip")
-    if force or not os.path.exists(_DEV_SO) or os.path.getmtime(_DEV_SO) < os.path.getmtime(src):
+    """Compile the device log-likelihood generator and the measurement probes for gfx950."""
+    srcs = [os.path.join(_DIR, "loglikes.hip"), os.path.join(_DIR, "probes.hip")]
+    if force or not os.path.exists(_DEV_SO) or os.path.getmtime(_DEV_SO) < max(os.path.getmtime(p) for p in srcs):
         hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
         subprocess.check_call([hipcc, "--offload-arch=gfx950", "-O3", "-ffp-contract=off",
                                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-                               "-fPIC", "-shared", "-o", _DEV_SO, src])
+                               "-fPIC", "-shared", "-o", _DEV_SO] + srcs)
     return _DEV_SO
 
 
@@ -151,11 +151,7 @@ def host_loglikes(seed: int, stream: int, frame0: int, n_frames: int, num_pdfs: 
     return out
 
 
-def device_loglikes(out, seed: int, stream: int, frame0: int, mu: float, sigma: float,
-                    boost: float = 6.0) -> None:
-    """Fill a contiguous float32 cuda tensor [n_frames, num_pdfs] with the same bytes as
-    host_loglikes, on the tensor's device and the current torch stream."""
-    import torch
+def _devlib():
     global _dev
     if _dev is None:
         if not os.path.exists(_DEV_SO):
@@ -164,11 +160,52 @@ def device_loglikes(out, seed: int, stream: int, frame0: int, mu: float, sigma: 
         _dev.synth_loglikes_device.argtypes = [C.c_uint64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                                C.c_float, C.c_float, C.c_float, C.c_void_p, C.c_int64,
                                                C.c_void_p]
+        _dev.probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.POINTER(C.c_float)]
+        _dev.probe_gather.argtypes = [C.c_void_p, C.c_uint32, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int,
+                                      C.c_void_p, C.POINTER(C.c_float)]
+    return _dev
+
+
+def probe_copy_gbs(nbytes: int = 1 << 30, reps: int = 5) -> float:
+    """Measured rate of a plain device copy of nbytes (read + written bytes per second, GB/s)."""
+    import torch
+    src = torch.ones(nbytes // 4, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    ms = C.c_float()
+    rc = _devlib().probe_copy(src.data_ptr(), dst.data_ptr(), nbytes, reps, torch.cuda.current_stream().cuda_stream, C.byref(ms))
+    if rc:
+        raise RuntimeError(f"probe_copy failed ({rc})")
+    return 2.0 * nbytes / (ms.value * 1e-3) / 1e9
+
+
+def probe_gather(table_bytes: int, lanes: int, threads: int, inflight: int = 4, steps: int = 64, reps: int = 3) -> dict:
+    """12-byte records fetched at random from a table of table_bytes, lanes x threads threads with
+    `inflight` independent loads each: records per second and the rate in 64-byte lines."""
+    import torch
+    n = table_bytes // 12
+    table = torch.zeros(n * 3, dtype=torch.int32, device="cuda")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ms = C.c_float()
+    rc = _devlib().probe_gather(table.data_ptr(), n, lanes, threads, steps, inflight, sink.data_ptr(), reps,
+                                torch.cuda.current_stream().cuda_stream, C.byref(ms))
+    if rc:
+        raise RuntimeError(f"probe_gather failed ({rc})")
+    recs = lanes * threads * steps * max(1, (8 if inflight >= 8 else 4 if inflight >= 4 else 1))
+    return dict(records_per_s=recs / (ms.value * 1e-3), line_gbs=recs * 64 / (ms.value * 1e-3) / 1e9,
+                record_gbs=recs * 12 / (ms.value * 1e-3) / 1e9)
+
+
+def device_loglikes(out, seed: int, stream: int, frame0: int, mu: float, sigma: float,
+                    boost: float = 6.0) -> None:
+    """Fill a contiguous float32 cuda tensor [n_frames, num_pdfs] with the same bytes as
+    host_loglikes, on the tensor's device and the current torch stream."""
+    import torch
+    _devlib()
     assert out.is_cuda and out.dtype == torch.float32 and out.dim() == 2 and out.is_contiguous()
     n_frames, num_pdfs = out.shape
     if n_frames == 0:
         return
-    rc = _dev.synth_loglikes_device(seed, stream, frame0, n_frames, num_pdfs, mu, sigma, boost,
+    rc = _devlib().synth_loglikes_device(seed, stream, frame0, n_frames, num_pdfs, mu, sigma, boost,
                                     out.data_ptr(), out.stride(0),
                                     torch.cuda.current_stream(out.device).cuda_stream)
     if rc:

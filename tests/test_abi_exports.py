@@ -11,7 +11,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "wfst_decode.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(wfst_decode_\w+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(wfst_(?:decode|mux)_\w+)\s*\(", text)))
 
 
 @pytest.fixture(scope="module")
@@ -44,6 +44,11 @@ def test_strerror_and_null_arguments(B):
     assert L.wfst_decode_snapshot_wait(None, 1) == B.WFST_E_INVALID_ARG
     assert L.wfst_decode_snapshot_best_path_batch(None, 1, None, 0, 0, None, 0, None, None, None, None) == B.WFST_E_INVALID_ARG
     assert L.wfst_decode_snapshot_lattice_arcs(None, 1, None, 0, None, None, None, 0, 0, None, None) == B.WFST_E_INVALID_ARG
+    assert L.wfst_decode_final_lattice_noalloc(None, 0, 0, None, 0, None, None) == B.WFST_E_INVALID_ARG
+    assert L.wfst_mux_create(None, None) == B.WFST_E_INVALID_ARG
+    assert L.wfst_mux_submit(None, 0, None, 0, 0) == B.WFST_E_INVALID_ARG
+    assert L.wfst_mux_step(None, None, None) == B.WFST_E_INVALID_ARG
+    assert L.wfst_mux_pending(None) == 0 and L.wfst_mux_stats(None, None, None) == B.WFST_E_INVALID_ARG
 
 
 def test_malformed_graphs_are_rejected_before_any_device_work(B):
