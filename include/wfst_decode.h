@@ -265,7 +265,8 @@ int wfst_decode_snapshot_lattice_arcs(wfst_decoder_t *decoder, int64_t snapshot_
  * use_final and one holds a token) minus the best such cost.  An arc is kept iff te of its
  * destination + its extra cost <= lattice_beam.  The kept arcs are copied to `out` (HOST or
  * DEVICE as flagged) in no particular order; WFST_E_CAPACITY with *n = needed if cap is too
- * small.  info->density = kept arcs per frame.  Synchronises; allocates scratch. */
+ * small.  info->density = kept arcs per frame.  Synchronises.  (The single-channel form of
+ * wfst_decode_final_lattice_batch.) */
 typedef struct {
   int64_t arcs_in;        /* buffered arcs examined                        */
   int64_t arcs_kept;
@@ -277,6 +278,21 @@ typedef struct {
 int wfst_decode_final_lattice(wfst_decoder_t *decoder, int32_t channel, int32_t use_final,
                               wfst_lat_arc_t *out, int64_t cap, int64_t *n, int32_t out_is_device,
                               wfst_lattice_info_t *info);
+
+/* The final lattices of several channels in one pass (Section 3.4; lattice density as in Section
+ * 4.1): one workgroup per channel computes the extra costs, then the surviving arcs of all
+ * listed channels are packed into `out` (HOST or DEVICE as flagged): channel i's at
+ * out[offsets[i] .. offsets[i+1]) (offsets: HOST [n + 1]).  info, status: HOST [n]; status[i] is
+ * the channel's own result (0, its sticky error, or WFST_E_DEAD_CHANNEL); a channel with an
+ * error contributes no arcs.  The scratch of the pass (4 bytes per token of history capacity and
+ * 8 bytes per frame, for every channel) is allocated when the decoder is created with
+ * lattice_on, so the call itself allocates nothing on the device when `out` is device memory.
+ * If cap < offsets[n]: WFST_E_CAPACITY, offsets / info / status are still filled in, no arc is
+ * written.  Nothing is drained.  Synchronises. */
+int wfst_decode_final_lattice_batch(wfst_decoder_t *decoder, const int32_t *channels, int32_t n,
+                                    int32_t use_final, wfst_lat_arc_t *out, int64_t cap,
+                                    int64_t *offsets, int32_t out_is_device,
+                                    wfst_lattice_info_t *info, int32_t *status);
 
 /* wfst_decode_final_lattice for callers that cannot allocate device memory (code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same result, but the

@@ -25,7 +25,7 @@ EXPORTS = [
     "wfst_decode_destroy", "wfst_decode_state_bytes", "wfst_decode_init_channels", "wfst_decode_free_channels",
     "wfst_decode_advance", "wfst_decode_best_path_batch", "wfst_decode_best_path", "wfst_decode_best_path_arcs",
     "wfst_decode_lattice_arcs", "wfst_decode_lattice_arcs_batch", "wfst_decode_advance_snapshots",
-    "wfst_decode_snapshot_wait", "wfst_decode_snapshot_best_path_batch", "wfst_decode_snapshot_lattice_arcs", "wfst_decode_final_lattice", "wfst_decode_final_lattice_noalloc", "wfst_decode_tokens", "wfst_decode_stats", "wfst_decode_set_profiling",
+    "wfst_decode_snapshot_wait", "wfst_decode_snapshot_best_path_batch", "wfst_decode_snapshot_lattice_arcs", "wfst_decode_final_lattice", "wfst_decode_final_lattice_batch", "wfst_decode_final_lattice_noalloc", "wfst_decode_tokens", "wfst_decode_stats", "wfst_decode_set_profiling",
     "wfst_decode_profile", "wfst_decode_strerror",
     "wfst_mux_create", "wfst_mux_destroy", "wfst_mux_submit", "wfst_mux_step", "wfst_mux_pending", "wfst_mux_stats",
 ]
@@ -93,6 +93,7 @@ def lib():
         L.wfst_decode_snapshot_best_path_batch.argtypes = [vp, i64, vp, i32, i32, vp, i32, vp, vp, vp, vp]
         L.wfst_decode_snapshot_lattice_arcs.argtypes = [vp, i64, vp, i32, vp, vp, vp, i64, i32, C.POINTER(i64), C.POINTER(vp)]
         L.wfst_decode_final_lattice.argtypes = [vp, i32, i32, vp, i64, C.POINTER(i64), i32, C.POINTER(wfst_lattice_info_t)]
+        L.wfst_decode_final_lattice_batch.argtypes = [vp, vp, i32, i32, vp, i64, vp, i32, vp, vp]
         L.wfst_decode_final_lattice_noalloc.argtypes = [vp, i32, i32, vp, i64, C.POINTER(i64), C.POINTER(wfst_lattice_info_t)]
         L.wfst_decode_tokens.argtypes = [vp, i32, i32, vp, i32, C.POINTER(i32)]
         L.wfst_decode_stats.argtypes = [vp, i32, C.POINTER(wfst_stats_t)]
@@ -366,6 +367,24 @@ class WfstDecoder:
                 continue
             _check(rc, "wfst_decode_final_lattice")
             return out[:n.value].copy(), {k: getattr(info, k) for k, _ in wfst_lattice_info_t._fields_}
+
+    def final_lattice_batch(self, channels, use_final: bool = True, cap: int = 1 << 20):
+        """wfst_decode_final_lattice_batch with HOST output: (records, offsets int64[n+1], infos (list of dicts),
+        status int32[n])."""
+        ch = np.ascontiguousarray(channels, np.int32)
+        n = len(ch)
+        while True:
+            out = np.zeros(max(cap, 1), LAT_DTYPE)
+            offs, st = np.zeros(n + 1, np.int64), np.zeros(n, np.int32)
+            info = (wfst_lattice_info_t * max(n, 1))()
+            rc = lib().wfst_decode_final_lattice_batch(self.h, ch.ctypes.data, n, int(use_final), out.ctypes.data, cap,
+                                                       offs.ctypes.data, 0, C.cast(info, C.c_void_p), st.ctypes.data)
+            if rc == WFST_E_CAPACITY:
+                cap = int(offs[n])
+                continue
+            _check(rc, "wfst_decode_final_lattice_batch")
+            infos = [{k: getattr(info[i], k) for k, _ in wfst_lattice_info_t._fields_} for i in range(n)]
+            return out[:offs[n]].copy(), offs, infos, st
 
     def final_lattice_device(self, channel: int, use_final: bool, out_ptr: int, cap: int, noalloc: bool = False):
         """wfst_decode_final_lattice with DEVICE output (out_ptr: device address of cap records), or its

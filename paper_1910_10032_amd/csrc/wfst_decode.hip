@@ -52,7 +52,9 @@ struct wfst_decoder {
   std::vector<int32_t> staged_chans;    // what d_chans currently holds
   PathOut *d_pathout = nullptr;
   void *d_stage = nullptr; size_t stage_bytes = 0;
-  void *d_stage2 = nullptr; size_t stage2_bytes = 0;   // scratch of the final-lattice pass
+  uint32_t *fl_te = nullptr;            // final-lattice scratch [num_channels][hist_cap]: extra cost of every kept token
+  long long *fl_rs = nullptr;           // [num_channels][max_frames + 3]: first lattice record of every frame
+  LatticeInfoDev *fl_info = nullptr;    // [num_channels]
   unsigned long long *d_cnt = nullptr;
   long long *d_offs = nullptr;          // readout scratch [max(num_channels, max_lanes) + 1]
   hipStream_t last_stream = nullptr;    // stream of the last advance call; readouts use it
@@ -346,6 +348,11 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
 #endif
   if (!rc) rc = dev_alloc(d, &d->d_offs, std::max(nc, nl) + 1);
   if (!rc) rc = dev_alloc(d, &d->d_ranges, 2 * std::max(nc, nl) + 1);
+  if (!rc && c.lattice_on) {
+    rc = dev_alloc(d, &d->fl_te, nc * (size_t)D.hist_cap);
+    if (!rc) rc = dev_alloc(d, &d->fl_rs, nc * (size_t)(c.max_frames + 3));
+    if (!rc) rc = dev_alloc(d, &d->fl_info, nc);
+  }
   D.n_blk = c.snapshot_blocks; D.blk_cap = c.snapshot_block_capacity;
   if (!rc && D.n_blk > 0) {
     rc = dev_alloc(d, &D.blk, (size_t)D.n_blk);
@@ -382,7 +389,6 @@ void wfst_decode_destroy(wfst_decoder_t *d) {
   (void)hipDeviceSynchronize();
   for (void *p : d->allocs) (void)hipFree(p);
   if (d->d_stage) (void)hipFree(d->d_stage);
-  if (d->d_stage2) (void)hipFree(d->d_stage2);
   for (int i = 0; i < PARAM_RING; ++i) {
     if (d->h_params[i]) (void)hipHostFree(d->h_params[i]);
     if (d->param_ev[i]) (void)hipEventDestroy(d->param_ev[i]);
@@ -746,46 +752,69 @@ int wfst_decode_snapshot_lattice_arcs(wfst_decoder_t *d, int64_t snapshot_id, co
   return 0;
 }
 
-int wfst_decode_final_lattice(wfst_decoder_t *d, int32_t channel, int32_t use_final, wfst_lat_arc_t *out, int64_t cap,
-                              int64_t *n, int32_t out_is_device, wfst_lattice_info_t *info) {
-  if (!d || !n || !info || cap < 0 || (cap > 0 && !out)) return WFST_E_INVALID_ARG;
-  int rc = check_channels(d, &channel, 1, true);
+// The final-lattice pass over the staged channel list: extra costs and counts, offsets, emission.
+// te / rs / info: the scratch (per channel id with the strides given, or one area with strides 0).
+static int final_lattice_launch(wfst_decoder *d, int32_t n, int32_t use_final, uint32_t *te, long long te_stride, long long *rs,
+                                long long rs_stride, LatticeInfoDev *info, LatRec *dst, int64_t cap) {
+  hipStream_t st = d->last_stream;
+  hipLaunchKernelGGL(k_final_lattice_te, dim3(n), dim3(1024), 0, st, d->dev, (const int32_t *)d->d_chans, use_final, te, te_stride,
+                     rs, rs_stride, info);
+  hipLaunchKernelGGL(k_final_lattice_offsets, dim3(1), dim3(1024), 0, st, (const LatticeInfoDev *)info, n, d->d_offs);
+  hipLaunchKernelGGL(k_final_lattice_emit, dim3(n), dim3(1024), 0, st, d->dev, (const int32_t *)d->d_chans, n, (const uint32_t *)te,
+                     te_stride, (const long long *)d->d_offs, dst, (long long)cap, (const LatticeInfoDev *)info);
+  HIP_TRY(hipGetLastError());
+  return 0;
+}
+
+static void fill_info(const LatticeInfoDev &li, wfst_lattice_info_t *info) {
+  info->arcs_in = li.arcs_in; info->arcs_kept = li.arcs_kept; info->frames = li.frames;
+  info->reached_final = li.reached_final; info->best_cost = li.best_cost;
+  info->density = (float)((double)li.arcs_kept / (double)std::max(li.frames - 1, 1));
+}
+
+int wfst_decode_final_lattice_batch(wfst_decoder_t *d, const int32_t *channels, int32_t n, int32_t use_final, wfst_lat_arc_t *out,
+                                    int64_t cap, int64_t *offsets, int32_t out_is_device, wfst_lattice_info_t *info, int32_t *status) {
+  if (!d || n < 0 || cap < 0 || !offsets || (cap > 0 && !out) || (n > 0 && (!info || !status))) return WFST_E_INVALID_ARG;
+  offsets[0] = 0;
+  if (n == 0) return 0;
+  if (!d->fl_te) return WFST_E_INVALID_ARG;            // the decoder produces no lattice arcs
+  int rc = check_channels(d, channels, n, true);
   if (rc) return rc;
-  ChanState cs;
-  rc = read_chan(d, channel, &cs);
+  hipStream_t st = d->last_stream;
+  rc = stage_channels(d, st, channels, n);
   if (rc) return rc;
-  if (cs.status != 0) return cs.status;
-  // scratch: one word per kept token, one offset per frame, the info block
-  const size_t te_bytes = sizeof(uint32_t) * (size_t)std::max<long long>(cs.hist_used, 1);
-  const size_t rs_off = (te_bytes + 15) & ~(size_t)15;
-  const size_t info_off = rs_off + sizeof(long long) * ((size_t)cs.num_frames + 3);
-  const size_t need = info_off + sizeof(LatticeInfoDev);
-  if (need > d->stage2_bytes) {
-    if (d->d_stage2) HIP_TRY(hipFree(d->d_stage2));
-    d->d_stage2 = nullptr; d->stage2_bytes = 0;
-    HIP_TRY(hipMalloc(&d->d_stage2, need));
-    d->stage2_bytes = need;
-  }
   LatRec *dst = (LatRec *)out;
-  if (!out_is_device) {
+  if (!out_is_device) {                 // host output goes through device staging of the caller's capacity
+    if (sizeof(LatRec) * (size_t)std::max<int64_t>(cap, 1) > d->stage_bytes) HIP_TRY(hipStreamSynchronize(st));
     rc = ensure_stage(d, sizeof(LatRec) * (size_t)std::max<int64_t>(cap, 1));
     if (rc) return rc;
     dst = (LatRec *)d->d_stage;
   }
-  char *base = (char *)d->d_stage2;
-  hipLaunchKernelGGL(k_final_lattice, dim3(1), dim3(1024), 0, d->last_stream, d->dev, channel, use_final, (uint32_t *)base,
-                     (long long *)(base + rs_off), dst, (long long)cap, (LatticeInfoDev *)(base + info_off));
-  HIP_TRY(hipGetLastError());
-  LatticeInfoDev li;
-  HIP_TRY(copy_sync(d, &li, base + info_off, sizeof(li), hipMemcpyDeviceToHost));
-  if (li.status == WFST_E_CAPACITY) { *n = li.arcs_kept; return WFST_E_CAPACITY; }
-  if (li.status != 0) return li.status;
-  if (!out_is_device && li.arcs_kept > 0)
-    HIP_TRY(copy_sync(d, out, dst, sizeof(LatRec) * (size_t)li.arcs_kept, hipMemcpyDeviceToHost));
-  *n = li.arcs_kept;
-  info->arcs_in = li.arcs_in; info->arcs_kept = li.arcs_kept; info->frames = li.frames;
-  info->reached_final = li.reached_final; info->best_cost = li.best_cost;
-  info->density = (float)((double)li.arcs_kept / (double)std::max(li.frames - 1, 1));
+  rc = final_lattice_launch(d, n, use_final, d->fl_te, (long long)d->dev.hist_cap, d->fl_rs, (long long)d->cfg.max_frames + 3,
+                            d->fl_info, dst, cap);
+  if (rc) return rc;
+  std::vector<LatticeInfoDev> li((size_t)n);
+  HIP_TRY(copy_sync_on(st, li.data(), d->fl_info, sizeof(LatticeInfoDev) * (size_t)n, hipMemcpyDeviceToHost));
+  static_assert(sizeof(long long) == sizeof(int64_t), "offset width");
+  HIP_TRY(copy_sync_on(st, offsets, d->d_offs, sizeof(long long) * ((size_t)n + 1), hipMemcpyDeviceToHost));
+  for (int32_t i = 0; i < n; ++i) { status[i] = li[i].status; fill_info(li[i], info + i); }
+  if (offsets[n] > cap) return WFST_E_CAPACITY;
+  if (!out_is_device && offsets[n] > 0)
+    HIP_TRY(copy_sync_on(st, out, dst, sizeof(LatRec) * (size_t)offsets[n], hipMemcpyDeviceToHost));
+  return 0;
+}
+
+int wfst_decode_final_lattice(wfst_decoder_t *d, int32_t channel, int32_t use_final, wfst_lat_arc_t *out, int64_t cap,
+                              int64_t *n, int32_t out_is_device, wfst_lattice_info_t *info) {
+  if (!n || !info) return WFST_E_INVALID_ARG;
+  int64_t offs[2] = {0, 0};
+  int32_t st = 0;
+  wfst_lattice_info_t li{};
+  const int rc = wfst_decode_final_lattice_batch(d, &channel, 1, use_final, out, cap, offs, out_is_device, &li, &st);
+  if (rc == WFST_E_CAPACITY) { *n = offs[1]; return rc; }
+  if (rc) return rc;
+  if (st) return st;
+  *n = offs[1]; *info = li;
   return 0;
 }
 
@@ -798,24 +827,24 @@ int wfst_decode_final_lattice_noalloc(wfst_decoder_t *d, int32_t channel, int32_
   rc = read_chan(d, channel, &cs);
   if (rc) return rc;
   if (cs.status != 0) return cs.status;
-  // the same scratch layout as wfst_decode_final_lattice, inside the fixed array
+  // the pass's scratch inside the fixed array: extra costs, frame offsets, result block
   const size_t te_bytes = sizeof(uint32_t) * (size_t)std::max<long long>(cs.hist_used, 1);
   const size_t rs_off = (te_bytes + 15) & ~(size_t)15;
   const size_t info_off = rs_off + sizeof(long long) * ((size_t)cs.num_frames + 3);
   const size_t need = info_off + sizeof(LatticeInfoDev);
   if (need > NOALLOC_SCRATCH_BYTES) return WFST_E_SCRATCH_LIMIT;
   char *base = (char *)d->noalloc_scratch;          // the looked-up device address, never the array's name
-  hipLaunchKernelGGL(k_final_lattice, dim3(1), dim3(1024), 0, d->last_stream, d->dev, channel, use_final, (uint32_t *)base,
-                     (long long *)(base + rs_off), (LatRec *)out, (long long)cap, (LatticeInfoDev *)(base + info_off));
-  HIP_TRY(hipGetLastError());
+  HIP_TRY(copy_sync(d, d->d_chans, &channel, sizeof(int32_t), hipMemcpyHostToDevice));
+  d->staged_chans.clear();
+  rc = final_lattice_launch(d, 1, use_final, (uint32_t *)base, 0, (long long *)(base + rs_off), 0, (LatticeInfoDev *)(base + info_off),
+                            (LatRec *)out, cap);
+  if (rc) return rc;
   LatticeInfoDev li;
   HIP_TRY(copy_sync(d, &li, base + info_off, sizeof(li), hipMemcpyDeviceToHost));
-  if (li.status == WFST_E_CAPACITY) { *n = li.arcs_kept; return WFST_E_CAPACITY; }
   if (li.status != 0) return li.status;
   *n = li.arcs_kept;
-  info->arcs_in = li.arcs_in; info->arcs_kept = li.arcs_kept; info->frames = li.frames;
-  info->reached_final = li.reached_final; info->best_cost = li.best_cost;
-  info->density = (float)((double)li.arcs_kept / (double)std::max(li.frames - 1, 1));
+  if (li.arcs_kept > cap) return WFST_E_CAPACITY;
+  fill_info(li, info);
   return 0;
 }
 

@@ -521,9 +521,17 @@ __global__ void k_snapshot_ranges(DecDev D, const int32_t *chans, int n, long lo
 // negative) float bits, so the result does not depend on thread order.  One workgroup.
 struct LatticeInfoDev { long long arcs_in, arcs_kept; int32_t frames, reached_final, status, pad; float best_cost, pad2; };
 
-__global__ void __launch_bounds__(1024) k_final_lattice(DecDev D, int ch, int use_final, uint32_t *te, long long *rec_start,
-                                                        LatRec *out, long long cap, LatticeInfoDev *info) {
+// Pass 1, one workgroup per listed channel: the extra cost te of every kept token (into the
+// channel's scratch: te one word per token, rec_start one offset per frame) and the number of
+// arcs that survive, into info[blockIdx.x].  te_stride / rs_stride: distance between the
+// scratch areas of consecutive channel ids (0: a single area, for a call on one channel).
+__global__ void __launch_bounds__(1024) k_final_lattice_te(DecDev D, const int32_t *chans, int use_final, uint32_t *te_base,
+                                                           long long te_stride, long long *rs_base, long long rs_stride,
+                                                           LatticeInfoDev *info) {
   const int tid = threadIdx.x, NTH = 1024;
+  const int ch = chans[blockIdx.x];
+  uint32_t *te = te_base + (size_t)ch * (size_t)te_stride;
+  long long *rec_start = rs_base + (size_t)ch * (size_t)rs_stride;
   const ChanState *cs = D.chan + ch;
   const long long *foff = D.frame_off + (size_t)ch * (size_t)(D.max_frames + 2);
   const HTok *hist = D.hist + (size_t)ch * (size_t)D.hist_cap;
@@ -542,7 +550,7 @@ __global__ void __launch_bounds__(1024) k_final_lattice(DecDev D, int ch, int us
   const long long oT = T >= 0 ? foff[T] : 0;
   const int nT = T >= 0 ? (int)(foff[T + 1] - oT) : 0;
   if (!readable || nT == 0) {
-    if (tid == 0) { LatticeInfoDev li{n_rec, 0, T + 1, 0, readable ? E_DEAD_CHANNEL : st, 0, 0.f, 0.f}; *info = li; }
+    if (tid == 0) { LatticeInfoDev li{n_rec, 0, T + 1, 0, readable ? E_DEAD_CHANNEL : st, 0, 0.f, 0.f}; info[blockIdx.x] = li; }
     return;
   }
   if (tid == 0) { s_best_f = KEY_NONE; s_best_n = KEY_NONE; s_kept = 0; }
@@ -609,19 +617,66 @@ __global__ void __launch_bounds__(1024) k_final_lattice(DecDev D, int ch, int us
       __syncthreads();
     }
   }
+  unsigned long long kept = 0;
   for (long long i = tid; i < n_rec; i += NTH) {
     const LatInt r = lat(i);
     const float v = __uint_as_float(ld32(&te[foff[r.frame] + r.dst])) + r.extra;
-    if (v <= D.lattice_beam) {
-      const unsigned long long p = atomicAdd(&s_kept, 1ull);
-      if ((long long)p < cap) out[p] = LatRec{r.frame, D.g.orig[r.arc], r.extra};
-    }
+    kept += v <= D.lattice_beam ? 1 : 0;
   }
+  if (kept) atomicAdd(&s_kept, kept);
   __syncthreads();
   if (tid == 0) {
     LatticeInfoDev li{n_rec, (long long)s_kept, T + 1, any_final ? 1 : 0, 0, 0, best, 0.f};
-    if ((long long)s_kept > cap) li.status = E_CAPACITY;
-    *info = li;
+    info[blockIdx.x] = li;
+  }
+}
+
+// offs[0..n]: exclusive prefix sums of the kept-arc counts of pass 1 (one block).
+__global__ void __launch_bounds__(1024) k_final_lattice_offsets(const LatticeInfoDev *info, int n, long long *offs) {
+  __shared__ long long part[1024];
+  const int tid = threadIdx.x;
+  const int per = (n + 1023) / 1024;
+  const int b = tid * per, e = min(n, b + per);
+  long long sum = 0;
+  for (int i = b; i < e; ++i) sum += info[i].status == 0 ? info[i].arcs_kept : 0;
+  part[tid] = sum;
+  __syncthreads();
+  for (int d = 1; d < 1024; d <<= 1) {
+    const long long v = tid >= d ? part[tid - d] : 0;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  long long run = part[tid] - sum;
+  for (int i = b; i < e; ++i) { offs[i] = run; run += info[i].status == 0 ? info[i].arcs_kept : 0; }
+  if (tid == 1023) offs[n] = part[1023];
+}
+
+// Pass 2: the surviving arcs of listed channel blockIdx.x, in the caller's form, at out[offs[blockIdx.x] ..).
+// Nothing is written if the caller's buffer cannot take all channels' arcs.
+__global__ void __launch_bounds__(1024) k_final_lattice_emit(DecDev D, const int32_t *chans, int n_ch, const uint32_t *te_base,
+                                                             long long te_stride, const long long *offs, LatRec *out,
+                                                             long long cap, const LatticeInfoDev *info) {
+  if (offs[n_ch] > cap || info[blockIdx.x].status != 0) return;
+  const int tid = threadIdx.x, NTH = 1024;
+  const int ch = chans[blockIdx.x];
+  const uint32_t *te = te_base + (size_t)ch * (size_t)te_stride;
+  const ChanState *cs = D.chan + ch;
+  const long long *foff = D.frame_off + (size_t)ch * (size_t)(D.max_frames + 2);
+  const LatInt *lat_ring = D.lat + (size_t)ch * (size_t)D.lat_cap;
+  const long long lat_first = cs->lat_head % D.lat_cap, lat_cap = D.lat_cap;
+  const long long n_rec = cs->lat_total - cs->lat_head;
+  LatRec *dst = out + offs[blockIdx.x];
+  __shared__ unsigned long long s_pos;
+  if (tid == 0) s_pos = 0;
+  __syncthreads();
+  for (long long i = tid; i < n_rec; i += NTH) {
+    const LatInt r = lat_ring[lat_first + i < lat_cap ? lat_first + i : lat_first + i - lat_cap];
+    const float v = __uint_as_float(te[foff[r.frame] + r.dst]) + r.extra;
+    if (v <= D.lattice_beam) {
+      const unsigned long long p = atomicAdd(&s_pos, 1ull);
+      dst[p] = LatRec{r.frame, D.g.orig[r.arc], r.extra};
+    }
   }
 }
 
