@@ -28,7 +28,10 @@
  *  - Errors that concern one channel (token/lattice/history overflow, a channel with no
  *    surviving token, NaN or +inf in the scores it read) are sticky for that channel,
  *    stop that channel at the frame where they occur, and never disturb other channels.
- *  - A graph may be shared by several decoders.  A decoder is not thread-safe.
+ *  - A graph may be shared by several decoders.  A decoder is not thread-safe.  Its advance
+ *    calls are ordered one after the other even when they are given different streams (the
+ *    lanes' scratch belongs to the decoder): a call on another stream than the previous one
+ *    waits for that one.  Decoders of their own do run side by side.
  */
 #ifndef WFST_DECODE_H
 #define WFST_DECODE_H
@@ -128,8 +131,9 @@ typedef struct {
 
 /* Validate and upload a graph.  WFST_E_BAD_GRAPH if offsets are not monotone, a
  * destination or the start state is out of range, an ilabel is negative or exceeds
- * num_pdfs, a weight is not finite, a non-emitting weight is negative, a final cost is
- * NaN or -inf, or num_states + num_arcs >= 2^31 - 1.  On the device the graph takes
+ * num_pdfs, a weight is not finite, a non-emitting weight is negative, the non-emitting arcs
+ * of weight zero form a cycle (ties around such a cycle would let back-pointers loop), a final
+ * cost is NaN or -inf, or num_states + num_arcs >= 2^31 - 1.  On the device the graph takes
  * 12*(num_states + num_arcs) bytes for decoding (the paper's Eq. 1 plus 4 bytes per
  * non-emitting arc) and 8*(num_states + num_arcs) bytes used only by readouts. */
 int wfst_decode_graph_load(const wfst_csr_t *csr, wfst_graph_t **out);

@@ -282,7 +282,9 @@ int64_t oracle_lattice(const void *d, int32_t from_frame, int32_t *frame, uint32
 
 // Best path.  arcs (caller ids, forward order) and words (non-zero olabels, forward order).
 // Returns 0, or -1 if there is no token, -2 if a buffer is too small, -3 if a token's
-// best incoming arc starts from a state that holds no token.
+// best incoming arc starts from a state that holds no token or the back-pointers loop (both
+// can only happen on graphs the decoding library refuses or warns about: zero-weight epsilon
+// cycles, epsilon arcs into lower state ids with cost ties).
 int32_t oracle_best_path(const void *d, int32_t use_final, int32_t *words, int32_t words_cap, int32_t *n_words,
                          int64_t *arcs, int32_t arcs_cap, int32_t *n_arcs, float *total_cost, int32_t *reached_final) {
   const Decoder &D = *(const Decoder *)d; const Graph &g = *D.g;
@@ -302,7 +304,10 @@ int32_t oracle_best_path(const void *d, int32_t use_final, int32_t *words, int32
     for (auto &kv : last) if (!found || okey(kv.second.cost) < okey(bc)) { found = true; bs = kv.first; bc = kv.second.cost; }
   std::vector<int64_t> path;
   int32_t f = (int32_t)D.frames.size() - 1, s = bs;
+  size_t tokens_in_all = 0;                        // a trace longer than this revisits a token: back-pointers that loop
+  for (auto &fr : D.frames) tokens_in_all += fr.size();
   for (;;) {
+    if (path.size() > tokens_in_all) return -3;
     auto it = D.frames[f].find(s);
     if (it == D.frames[f].end()) return -3;
     if (it->second.in_rank == NO_ARC) break;

@@ -58,6 +58,8 @@ struct wfst_decoder {
   unsigned long long *d_cnt = nullptr;
   long long *d_offs = nullptr;          // readout scratch [max(num_channels, max_lanes) + 1]
   hipStream_t last_stream = nullptr;    // stream of the last advance call; readouts use it
+  hipEvent_t last_advance = nullptr;    // recorded behind the last advance call
+  bool have_last_advance = false;
   hipStream_t side_stream = nullptr;    // snapshot readouts run here, beside the decoding
   long long *h_sealed = nullptr;        // pinned [max_lanes]: id of the last snapshot each lane sealed
   int64_t next_snap_id = 1;
@@ -204,6 +206,35 @@ int wfst_decode_graph_load(const wfst_csr_t *csr, wfst_graph_t **out) {
     if (csr->ilabel[a] < 0 || csr->ilabel[a] > csr->num_pdfs) return WFST_E_BAD_GRAPH;
     if (!std::isfinite(csr->weight[a])) return WFST_E_BAD_GRAPH;
     if (csr->ilabel[a] == 0 && csr->weight[a] < 0.f) return WFST_E_BAD_GRAPH;
+  }
+  // Zero-weight epsilon cycles are refused: around such a cycle all candidates tie in cost, the
+  // tie goes to the smaller arc index, and a token's best incoming arc can then be the cycle's own
+  // arc - back-pointers that loop.  (Kahn's algorithm on the sub-graph of zero-weight epsilon arcs.)
+  {
+    std::vector<int64_t> zero_arcs;
+    try {
+      for (int64_t a = 0; a < E; ++a) if (csr->ilabel[a] == 0 && csr->weight[a] == 0.f) zero_arcs.push_back(a);
+      if (!zero_arcs.empty()) {
+        std::vector<int32_t> src_of(zero_arcs.size()), indeg(Q, 0), order;
+        std::vector<int64_t> first(Q + 1, 0);
+        for (size_t k = 0; k < zero_arcs.size(); ++k) {
+          const int64_t a = zero_arcs[k];
+          const int32_t s = (int32_t)(std::upper_bound(csr->row_offsets, csr->row_offsets + Q + 1, a) - csr->row_offsets) - 1;
+          src_of[k] = s; ++first[s + 1]; ++indeg[csr->nextstate[a]];
+        }
+        for (int32_t s = 0; s < Q; ++s) first[s + 1] += first[s];
+        std::vector<int32_t> dst_by_src(zero_arcs.size());
+        std::vector<int64_t> fill(first.begin(), first.end() - 1);
+        for (size_t k = 0; k < zero_arcs.size(); ++k) dst_by_src[(size_t)fill[src_of[k]]++] = csr->nextstate[zero_arcs[k]];
+        for (int32_t s = 0; s < Q; ++s) if (indeg[s] == 0) order.push_back(s);
+        size_t done = 0;
+        while (done < order.size()) {
+          const int32_t s = order[done++];
+          for (int64_t k = first[s]; k < first[s + 1]; ++k) if (--indeg[dst_by_src[(size_t)k]] == 0) order.push_back(dst_by_src[(size_t)k]);
+        }
+        if (order.size() != (size_t)Q) return WFST_E_BAD_GRAPH;
+      }
+    } catch (const std::bad_alloc &) { return WFST_E_DEVICE; }
   }
   // record layout: header of state s at handle[s] = s + (arcs of earlier states)
   const size_t R = (size_t)Q + (size_t)E;
@@ -367,6 +398,7 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
            hipEventCreateWithFlags(&d->param_ev[i], hipEventDisableTiming) == hipSuccess;
     ok = ok && hipMemset(D.snap, 0, sizeof(ChanSnap) * nc * SNAP_RING) == hipSuccess &&
          hipStreamCreateWithFlags(&d->side_stream, hipStreamNonBlocking) == hipSuccess &&
+         hipEventCreateWithFlags(&d->last_advance, hipEventDisableTiming) == hipSuccess &&
          hipHostMalloc((void **)&d->h_sealed, sizeof(long long) * nl) == hipSuccess;
     if (ok) {
       std::memset(d->h_sealed, 0, sizeof(long long) * nl);
@@ -395,6 +427,7 @@ void wfst_decode_destroy(wfst_decoder_t *d) {
   }
   for (auto &p : d->prof_events) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
   if (d->side_stream) (void)hipStreamDestroy(d->side_stream);
+  if (d->last_advance) (void)hipEventDestroy(d->last_advance);
   if (d->h_sealed) (void)hipHostFree(d->h_sealed);
   delete d;
 }
@@ -463,6 +496,10 @@ static int advance_impl(wfst_decoder_t *d, const int32_t *channels, int32_t n_la
     lp[i] = LaneParam{loglikes[i], channels[i], n_frames[i], strides[i], snapshot_every, id0, n_snaps, 0};
     d->frames_fed[channels[i]] += n_frames[i];
   }
+  // The lanes' scratch and parameter block belong to the decoder, not to the call: a call on
+  // another stream than the previous one first waits for that one.
+  if (d->have_last_advance && (hipStream_t)stream != d->last_stream)
+    HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, d->last_advance, 0));
   d->last_stream = (hipStream_t)stream;
   if (n_snaps > 0 && d->dev.n_blk > 0) {     // the blocks these snapshots will fill start empty
     hipLaunchKernelGGL(k_reset_blocks, dim3((n_snaps + 63) / 64), dim3(64), 0, (hipStream_t)stream, d->dev, (long long)id0, n_snaps);
@@ -471,6 +508,8 @@ static int advance_impl(wfst_decoder_t *d, const int32_t *channels, int32_t n_la
   }
   rc = launch_lanes(d, lp, 0, (hipStream_t)stream);
   if (rc) return rc;
+  HIP_TRY(hipEventRecord(d->last_advance, (hipStream_t)stream));
+  d->have_last_advance = true;
   if (n_snaps > 0) {
     d->next_snap_id += n_snaps;
     d->snap_calls.push_back({id0, n_snaps, n_lanes, (hipStream_t)stream});

@@ -81,3 +81,9 @@ def test_malformed_graphs_are_rejected_before_any_device_work(B):
     ]
     for edit in cases:
         assert load(variant(edit)) == B.WFST_E_BAD_GRAPH
+    # non-emitting arcs of weight zero that form a cycle (1 -> 2 -> 1), also through a longer detour
+    cyc = [(0, 1, 1, 0, 1.0), (1, 2, 0, 0, 0.0), (2, 1, 0, 0, 0.0)]
+    assert load(graph_from_arcs(3, cyc, 2)) == B.WFST_E_BAD_GRAPH
+    cyc = [(0, 1, 1, 0, 1.0), (1, 2, 0, 0, 0.0), (2, 3, 0, 0, 0.0), (3, 3, 1, 0, 1.0), (3, 1, 0, 0, 0.0), (3, 0, 0, 0, 0.0)]
+    assert load(graph_from_arcs(4, cyc, 2)) == B.WFST_E_BAD_GRAPH
+    assert load(graph_from_arcs(2, [(0, 1, 1, 0, 1.0), (1, 1, 0, 0, 0.0)], 2)) == B.WFST_E_BAD_GRAPH     # a self loop

@@ -296,3 +296,20 @@ def test_arcs_expanded_counts_epsilon_degrees_before_the_max_active_cut(seed):
         assert d.arcs_expanded == total
     assert differs >= 1                            # counting after the cut would give another number
     assert d.max_tokens_pre_prune > alpha and d.max_tokens == alpha
+
+
+# ---- back-pointers that loop ---------------------------------------------------------------
+
+def test_best_path_on_a_zero_weight_epsilon_cycle_ends_with_an_error():
+    """Start state 3, emitting arc 3 -> 1, epsilon arcs 1 -> 2 and 2 -> 1 of weight zero.  Around the
+    cycle all candidates tie; the tie goes to the smaller arc rank, and the arcs of states 1 and 2
+    rank below the arc of state 3: tokens 1 and 2 point at each other.  The trace must stop with an
+    error instead of running for ever (the decoding library refuses to load such a graph)."""
+    arcs = [(1, 2, 0, 0, 0.0), (2, 1, 0, 0, 0.0), (3, 1, 1, 0, 1.0)]
+    g = graph_from_arcs(4, arcs, 1, start=3)
+    d = oracle.OracleDecoder(oracle.OracleGraph(g), 5.0, 5.0, BIG_ALPHA)
+    d.advance(np.zeros((1, 1), F32))
+    st, co, ia = d.tokens(1)
+    assert st.tolist() == [1, 2] and co.tolist() == [1.0, 1.0] and ia.tolist() == [1, 0]
+    with pytest.raises(RuntimeError):
+        d.best_path(False)
