@@ -148,14 +148,25 @@ void wfst_decode_destroy(wfst_decoder_t *decoder);
 /* Device bytes held per parked channel, per lane, and in total. */
 int wfst_decode_state_bytes(const wfst_decoder_t *decoder, int64_t *per_channel, int64_t *per_lane, int64_t *total);
 
-/* Start (or restart) streams: each listed channel gets the start token and its closure
- * as frame 0.  channels: HOST [n], distinct, each in [0, num_channels); n may exceed
+/* Start (or restart) streams (Section 3.1: a channel holds the state of one audio stream
+ * between batches; Section 3, first paragraph: decoding starts from the graph's start state
+ * and follows chains of non-emitting arcs before the first frame): each listed channel gets
+ * the start token at cost 0 and its non-emitting closure within the beam as frame 0.  channels: HOST [n], distinct, each in [0, num_channels); n may exceed
  * max_lanes (processed in groups).  Synchronises with the device before returning. */
 int wfst_decode_init_channels(wfst_decoder_t *decoder, const int32_t *channels, int32_t n);
-/* Mark channels unused; their buffers are reused by the next init. */
+/* Mark channels unused (Section 3.1: a channel is released when its stream ends); their
+ * buffers are reused by the next init. */
 int wfst_decode_free_channels(wfst_decoder_t *decoder, const int32_t *channels, int32_t n);
 
-/* Advance n_lanes channels: lane i consumes n_frames[i] rows of scores.
+/* Advance n_lanes channels (Section 3.1: a batch works on up to max_lanes channels, one lane
+ * each).  Per frame and lane (Section 3, first paragraph; Fig. 1; Section 3.3): every
+ * emitting arc out of a token is expanded against the frame's scores, cost = (token cost +
+ * arc weight) - loglike[pdf]; candidates above best + beam are dropped and each state keeps
+ * its minimum; chains of non-emitting arcs are followed until nothing changes; if more than
+ * max_active tokens remain the max_active best are kept and the cost of the last one becomes
+ * the frame's cutoff (the adaptive beam); every arc into a kept token within that cutoff and
+ * the lattice beam is recorded with its extra cost (Section 3.4).
+ * Lane i consumes n_frames[i] rows of scores.
  *   channels  HOST [n_lanes]  distinct initialised channel ids, n_lanes <= max_lanes
  *   loglikes  HOST [n_lanes]  array of DEVICE pointers; lane i's rows are fp32
  *                             [n_frames[i]][strides[i]], already acoustically scaled;
@@ -169,7 +180,9 @@ int wfst_decode_advance(wfst_decoder_t *decoder, const int32_t *channels, int32_
                         const float *const *loglikes, const int32_t *strides,
                         const int32_t *n_frames, void *stream);
 
-/* Best path of each listed channel over all frames decoded so far.
+/* Best path of each listed channel over all frames decoded so far (the one-best result of
+ * Section 4, Table 2; Section 3.4: each token keeps its best incoming arc, which is what the
+ * trace follows back to the start token).
  *   use_final      1: minimise token cost + final cost over final states (falling back
  *                  to 0 when no final state holds a token); 0: minimise token cost
  *   words          HOST [n * words_cap]  channel i's non-zero olabels, in path order, at
@@ -182,16 +195,21 @@ int wfst_decode_best_path_batch(wfst_decoder_t *decoder, const int32_t *channels
                                 int32_t use_final, int32_t *words, int32_t words_cap,
                                 int32_t *n_words, float *total_cost, int32_t *reached_final,
                                 int32_t *status);
-/* Single-channel form; returns the channel's result code. */
+/* Single-channel form of wfst_decode_best_path_batch (same passages); returns the channel's
+ * result code. */
 int wfst_decode_best_path(wfst_decoder_t *decoder, int32_t channel, int32_t use_final,
                           int32_t *words, int32_t cap, int32_t *n_words, float *total_cost,
                           int32_t *reached_final);
-/* Arcs (caller's ids, path order) of the best path of one channel.  arcs: HOST [cap]. */
+/* Arcs (caller's ids, path order) of the best path of one channel: the chain of best
+ * incoming arcs of Section 3.4 itself, start token first.  arcs: HOST [cap]. */
 int wfst_decode_best_path_arcs(wfst_decoder_t *decoder, int32_t channel, int32_t use_final,
                                uint32_t *arcs, int32_t cap, int32_t *n_arcs, float *total_cost,
                                int32_t *reached_final);
 
-/* Drain the lattice arcs buffered for a channel since its last readout.  Records with
+/* Drain the lattice arcs buffered for a channel since its last readout (Section 3.4: per
+ * frame, one representative token per FST state, and every other arc that reaches the state
+ * within the beams kept with its extra cost = its cost minus the state's best; Section 3,
+ * Fig. 1: such per-frame results leave the decoder while it goes on).  Records with
  * frame < from_frame are discarded, the others are copied to `out` in no particular
  * order (HOST memory if out_is_device == 0, else DEVICE memory), and the buffer is
  * emptied.  If cap is too small: WFST_E_CAPACITY, *n = needed, nothing is drained.
@@ -200,7 +218,8 @@ int wfst_decode_best_path_arcs(wfst_decoder_t *decoder, int32_t channel, int32_t
 int wfst_decode_lattice_arcs(wfst_decoder_t *decoder, int32_t channel, int32_t from_frame,
                              wfst_lat_arc_t *out, int64_t cap, int64_t *n, int32_t out_is_device);
 
-/* Drain several channels at once into one buffer: channel i's arcs land at
+/* Drain several channels at once into one buffer (the batch form of
+ * wfst_decode_lattice_arcs; Section 3.4): channel i's arcs land at
  * out[offsets[i] .. offsets[i+1]) (offsets: HOST [n + 1]).  A channel stopped by an
  * overflow contributes nothing.  If cap < offsets[n]: WFST_E_CAPACITY, offsets are still
  * filled in, nothing is drained.  Synchronises. */
@@ -315,11 +334,14 @@ int wfst_decode_final_lattice_noalloc(wfst_decoder_t *decoder, int32_t channel, 
                                       wfst_lat_arc_t *out, int64_t cap, int64_t *n,
                                       wfst_lattice_info_t *info);
 
-/* Tokens kept for one frame of a channel (frame -1 = last), in no particular order.
+/* Tokens kept for one frame of a channel (frame -1 = last), in no particular order (Section
+ * 3.3: what survives the contraction of a frame - state, cost, best incoming arc).
  * out: HOST [cap].  A parity hook: the token history is what best_path walks. */
 int wfst_decode_tokens(wfst_decoder_t *decoder, int32_t channel, int32_t frame,
                        wfst_token_t *out, int32_t cap, int32_t *n);
 
+/* Counters of a channel (Section 4.1 discusses the decoder in terms of active tokens and
+ * expanded arcs; arcs_expanded is the numerator of the arcs-per-second figure). */
 int wfst_decode_stats(wfst_decoder_t *decoder, int32_t channel, wfst_stats_t *out);
 
 /* Per-kernel timing with HIP events on the stream of each call (off by default).  While
