@@ -70,6 +70,7 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
       S.tok_i[i] = (uint16_t)degree_info(rec[3 * (size_t)h], rec[3 * (size_t)h + 1]);
     }
     ctx.tok_valid = true;
+    ctx.scan_ready = false;
     lds_barrier();
   }
 
@@ -80,11 +81,14 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
   // fetches the state's epsilon arcs and parks them in LDS.
   auto claim = [&](int sl, uint32_t dw, uint32_t info, bool dup, unsigned long long *ctr, uint32_t qbase, uint32_t cbase) {
     const unsigned long long m_all = __ballot(1), m_new = __ballot(!dup);
+    const unsigned long long m_eps = __ballot(dup || ((info >> INFO_NP_SHIFT) & INFO_NP) != 0);   // entries a closure round has work for
     const int leader = __ffsll((long long)m_all) - 1;
     unsigned long long base = 0;
-    if (lane == leader) base = atomicAdd(ctr, ((unsigned long long)__popcll(m_new) << 32) | (unsigned long long)__popcll(m_all));
-    const uint32_t base_q = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)base, leader);
-    const uint32_t base_c = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(base >> 32), leader);
+    if (lane == leader)
+      base = atomicAdd(ctr, ((unsigned long long)__popcll(m_new) << CNT_CLAIM_SHIFT) | ((unsigned long long)__popcll(m_eps) << CNT_EPS_SHIFT) |
+                                (unsigned long long)__popcll(m_all));
+    const uint32_t base_q = (uint32_t)__builtin_amdgcn_readlane((int)((uint32_t)base & CNT_ENTRIES), leader);
+    const uint32_t base_c = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(base >> CNT_CLAIM_SHIFT), leader);
     const unsigned long long below = (1ull << lane) - 1ull;
     const uint32_t q = qbase + base_q + (uint32_t)__popcll(m_all & below);
     if (q >= (uint32_t)L::QCAP) atomicOr(ctr, CNT_RESTART);
@@ -138,13 +142,15 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
     }
   } else {
     for (int tb = 0; tb < n_in; tb += NT) {
-      const int i = tb + tid;
-      int ne = i < n_in ? (int)(S.tok_i[i] & INFO_NE) : 0;
-      if (ne == (int)INFO_NE) { atomicOr(&C.cnt[0], CNT_RESTART); ne = 0; }
-      const int inc = wave_incl_scan(ne);
-      S.scan[tid] = inc - ne;                  // exclusive within the wave
-      if (lane == 63) S.wtot[wid] = inc;
-      lds_barrier();
+      if (tb > 0 || !ctx.scan_ready) {         // (the first tile's sums are usually left by the previous frame)
+        const int i = tb + tid;
+        int ne = i < n_in ? (int)(S.tok_i[i] & INFO_NE) : 0;
+        if (ne == (int)INFO_NE) { atomicOr(&C.cnt[0], CNT_RESTART); ne = 0; }
+        const int inc = wave_incl_scan(ne);
+        S.scan[tid] = inc - ne;                // exclusive within the wave
+        if (lane == 63) S.wtot[wid] = inc;
+        lds_barrier();
+      }
       PHASE_MARK(1);
       int wb[NW];                              // arcs before each wave of the tile
       int total = 0;
@@ -273,10 +279,11 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
   // Round k works on the queue entries the round before appended: for each, the state's parked
   // epsilon arcs are relaxed from its current cost.  Entries appended in round k are counted by
   // counter (k + 1) % 3, which nobody touches in round k + 1, so one barrier per round is enough.
-  uint32_t w0 = 0, w1 = min((uint32_t)c0 & CNT_ENTRIES, (uint32_t)L::QCAP), nclaim = (uint32_t)(c0 >> 32);
+  uint32_t w0 = 0, w1 = min((uint32_t)c0 & CNT_ENTRIES, (uint32_t)L::QCAP), nclaim = (uint32_t)(c0 >> CNT_CLAIM_SHIFT);
+  uint32_t n_eps = (uint32_t)(c0 >> CNT_EPS_SHIFT) & CNT_EPS;      // entries of the window with epsilon arcs to relax
   int iters = 0;
   if (abort_code == 0) {
-    while (w0 < w1) {
+    while (n_eps > 0) {                        // (a window without such entries needs no round)
       unsigned long long *ctr = &C.cnt[(iters + 1) % 3];
       if (tid == 0) C.cnt[(iters + 2) % 3] = 0;
       for (uint32_t i = w0 + tid; i < w1; i += NT) {
@@ -299,7 +306,8 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
       }
       lds_barrier();
       const unsigned long long cv = uni(*ctr);   // stable: the next round appends to another counter
-      w0 = w1; w1 = min(w1 + ((uint32_t)cv & CNT_ENTRIES), (uint32_t)L::QCAP); nclaim += (uint32_t)(cv >> 32);
+      w0 = w1; w1 = min(w1 + ((uint32_t)cv & CNT_ENTRIES), (uint32_t)L::QCAP); nclaim += (uint32_t)(cv >> CNT_CLAIM_SHIFT);
+      n_eps = (uint32_t)(cv >> CNT_EPS_SHIFT) & CNT_EPS;
       ++iters;
       if (cv & CNT_RESTART) { abort_code = 1; break; }
     }
@@ -307,7 +315,7 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
   if (abort_code == 1) {                       // outgrew the LDS structures: wipe the table, the general frame redoes it
     for (int i = tid; i < L::SLOTS; i += NT) slots[i] = fresh;
     if (tid == 0) reset_ctr(C);
-    ctx.tok_valid = false;
+    ctx.tok_valid = false; ctx.scan_ready = false;
     __syncthreads();
 #ifdef WFST_PHASE_TIMING
     if (tid == 0) S.ph[13] += 1;
@@ -483,6 +491,16 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
       if (pos != POS_NONE && (uint32_t)slots[sl].val == NO_ARC) hist[out_base + pos] = HTok{S.tok_h[pos], 0.0f, NO_ARC, NO_ARC};
     }
   }
+  // the out-degree prefix sums the next frame's expansion starts from (its first tile), while
+  // this frame's stores drain: the barrier below publishes them with everything else
+  const bool scan_next = abort_code == 0 && ll_next != nullptr;
+  if (scan_next) {
+    int ne = (uint32_t)tid < n_out ? (int)(S.tok_i[tid] & INFO_NE) : 0;
+    if (ne == (int)INFO_NE) { atomicOr(&S.fc[ctx.par ^ 1].cnt[0], CNT_RESTART); ne = 0; }   // (the next frame's counter: reset long ago)
+    const int inc = wave_incl_scan(ne);
+    S.scan[tid] = inc - ne;
+    if (lane == 63) S.wtot[wid] = inc;
+  }
   lds_barrier();
   PHASE_MARK(9);
 
@@ -505,6 +523,7 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
 #endif
   if (abort_code != 0) ctx.status = abort_code;
   ctx.tok_valid = abort_code == 0;
+  ctx.scan_ready = scan_next;
   ctx.pending_clear = n_q;
   ctx.par ^= 1;
   return true;

@@ -80,7 +80,7 @@ __global__ void __launch_bounds__(NT, NT >= 512 ? 4 : 2) k_advance(DecDev D, con
     const long long o0 = uni(foff[ctx.nf - 1]), o1 = uni(foff[ctx.nf]);
     ctx.in_off = o0; ctx.n_in = (int)(o1 - o0);
   }
-  ctx.pending_clear = 0; ctx.par = 0; ctx.tok_valid = false;
+  ctx.pending_clear = 0; ctx.par = 0; ctx.tok_valid = false; ctx.scan_ready = false;
   __syncthreads();
   // Seal the lane's state as the next snapshot of this call.  With snapshot blocks the lattice
   // records not handed out yet move into the snapshot's block, in the caller's form (the lane
@@ -166,7 +166,7 @@ __global__ void __launch_bounds__(NT, NT >= 512 ? 4 : 2) k_advance(DecDev D, con
     ctx.status = uni(S.status); ctx.nf = uni(S.nf); ctx.n_in = uni(S.n_in); ctx.max_pre = uni(S.max_pre); ctx.max_post = uni(S.max_post);
     ctx.iters_max = uni(S.iters_max); ctx.in_off = uni(S.in_off); ctx.hist_used = uni(S.hist_used); ctx.lat_room = uni(S.lat_room);
     ctx.lat_total = uni(S.lat_total); ctx.lat_pos = uni(S.lat_pos); ctx.arcs_expanded = uni(S.arcs_expanded);
-    ctx.tok_valid = false;
+    ctx.tok_valid = false; ctx.scan_ready = false;
     __syncthreads();                                  // all have read the state before the next general frame rewrites it
   };
   const int nframes = is_init ? 1 : lp.n_frames;

@@ -76,8 +76,12 @@ constexpr uint32_t LQ_DUP = 0x8000u, LQ_SLOT = 0x7FFFu;
 //                                [11:0]  its emitting out-degree; after contraction: index of
 //                                        the kept token in the new frame, POS_NONE if dropped
 constexpr uint32_t POS_MASK = 0xFFFu, POS_NONE = 0xFFFu;
-constexpr unsigned long long CNT_RESTART = 1ull << 31;
-constexpr uint32_t CNT_ENTRIES = 0x7FFFFFFFu;
+// a round's counter: [63:42] states claimed, [41:21] entries appended that have epsilon arcs to
+// relax (claims of such states, re-expansion requests), [20] give the frame up, [19:0] entries appended
+constexpr unsigned long long CNT_RESTART = 1ull << 20;
+constexpr uint32_t CNT_ENTRIES = 0xFFFFFu;
+constexpr int CNT_EPS_SHIFT = 21, CNT_CLAIM_SHIFT = 42;
+constexpr uint32_t CNT_EPS = 0x1FFFFFu;
 constexpr uint32_t F_NAN = 1, F_TOKOVF = 2, F_LATOVF = 4, F_RESTART = 8;
 constexpr uint32_t KEY_NONE = 0xFFFFFFFFu;
 constexpr uint32_t KEY_PINF = 0xFF800000u;    // okey(+inf)
@@ -93,7 +97,7 @@ struct __align__(16) ENote {
 // Counters of one frame.  Two sets are used alternately, so that a frame can start while the
 // previous frame's values are still being read; the set not in use is reset in between.
 struct FrameCtr {
-  // per closure round: states claimed << 32 | CNT_RESTART | queue entries appended.  A round's
+  // per closure round: states claimed | entries with epsilon work | CNT_RESTART | entries appended.  A round's
   // counter is final at the round's barrier (the next round uses another one), so every thread
   // reads the same value there - also the request to give the frame up.
   unsigned long long cnt[3];
@@ -112,6 +116,7 @@ struct LaneCtx {
   uint32_t pending_clear;    // queue entries of the last light frame whose table slots are still to be cleared
   int par;                   // counter set the next light frame uses
   bool tok_valid;            // the LDS token list holds the frame the next one starts from
+  bool scan_ready;           // ... and the prefix sums of its first tile's out-degrees are in LDS too
 #ifdef WFST_PHASE_TIMING
   unsigned long long tlast;
 #endif
