@@ -111,6 +111,20 @@ typedef struct {
   int32_t frame_form;        /* 0 = per frame: the LDS-resident form for frames that fit it
                                 (when pdf ids fit in 16 bits), else the general form;
                                 1 = always the general form.  Results do not depend on it.  */
+  int32_t approximate;       /* 0 = exact max-active: exactly the max_active best tokens by
+                                (cost, state id), which is what the CPU checker computes.
+                                1 = the paper's histogram-based max-active (Section 4.1: the
+                                cut comes from a histogram and is "somewhat arbitrary"): when
+                                more than max_active tokens are within the beam, ONE histogram
+                                of 1024 equal-width cost bins between the frame's best and
+                                worst token places the cut at the upper edge of the bin in
+                                which the count reaches max_active.  All tokens up to that edge
+                                are kept (max_active plus at most that bin's population), the
+                                edge is the frame's effective cutoff, and the refinement passes
+                                of the exact selection are saved.  Deterministic, but not the
+                                checker's result wherever max-active binds; identical to the
+                                exact mode wherever it does not.  The default
+                                history_capacity is a quarter larger in this mode.            */
 } wfst_config_t;
 
 typedef struct { int32_t frame; uint32_t arc; float extra_cost; } wfst_lat_arc_t;

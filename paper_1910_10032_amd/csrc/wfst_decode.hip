@@ -320,11 +320,13 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
   if (c.token_capacity == 0) c.token_capacity = (int32_t)std::min<int64_t>(4ll * c.max_active, 1 << 28);
   if (c.token_capacity < 2 || c.token_capacity > (1 << 28)) return WFST_E_INVALID_ARG;
   if (c.aux_capacity == 0) c.aux_capacity = (int32_t)std::min<int64_t>(2ll * c.token_capacity, 1 << 29);
-  if (c.history_capacity == 0) c.history_capacity = ((int64_t)c.max_frames + 1) * c.max_active;
+  if (c.history_capacity == 0)          // (the approximate cut keeps somewhat more than max_active per frame)
+    c.history_capacity = ((int64_t)c.max_frames + 1) * (c.approximate ? (int64_t)c.max_active + c.max_active / 4 + 64 : (int64_t)c.max_active);
   if (c.lattice_capacity == 0) c.lattice_capacity = 64ll * c.max_active;
   if (c.snapshot_blocks < 0 || c.snapshot_block_capacity < 0) return WFST_E_INVALID_ARG;
   if (c.lane_threads != 0 && c.lane_threads != 256 && c.lane_threads != 512 && c.lane_threads != 1024) return WFST_E_INVALID_ARG;
   if (c.frame_form != 0 && c.frame_form != 1) return WFST_E_INVALID_ARG;
+  if (c.approximate != 0 && c.approximate != 1) return WFST_E_INVALID_ARG;
   if (!c.lattice_on) c.snapshot_blocks = 0;
   if (c.snapshot_blocks > 0 && c.snapshot_block_capacity == 0)
     c.snapshot_block_capacity = std::min<int64_t>(c.lattice_capacity, 4096ll * c.max_lanes);
@@ -349,6 +351,7 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
   D.auxcap = c.aux_capacity; D.tokcap = c.token_capacity; D.max_frames = c.max_frames; D.max_active = c.max_active;
   D.lattice_on = c.lattice_on ? 1 : 0; D.beam = c.beam; D.lattice_beam = c.lattice_beam;
   D.force_general = c.frame_form == 1 ? 1 : 0;
+  D.approximate = c.approximate;
   D.hist_cap = c.history_capacity; D.lat_cap = c.lattice_on ? c.lattice_capacity : 1;
   const size_t nc = (size_t)c.num_channels, nl = (size_t)c.max_lanes;
   int rc = 0;

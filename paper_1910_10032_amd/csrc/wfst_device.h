@@ -147,7 +147,8 @@ struct DecDev {
   uint32_t H;
   int32_t hbits, qcap, auxcap, tokcap, max_frames, max_active, lattice_on;
   float beam, lattice_beam;
-  int32_t force_general, pad1;   // 1: every frame takes the general form
+  int32_t force_general;         // 1: every frame takes the general form
+  int32_t approximate;           // 1: max-active by a single histogram cut (not exact)
   unsigned long long *dbg;   // phase timers of instrumented builds, else null
 };
 

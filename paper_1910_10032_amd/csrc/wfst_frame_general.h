@@ -245,7 +245,7 @@ __device__ void general_frame(const DecDev &D, LaneShared<NT> &S, const float *l
   if (abort_code == 0) {
     const uint32_t nclaim = S.nclaim;
     const uint32_t room = (uint32_t)min((long long)0x7FFFFFFF, D.hist_cap - out_base);
-    if (min(nclaim, (uint32_t)D.max_active) > room) abort_code = E_HISTORY_OVERFLOW;
+    if ((D.approximate ? nclaim : min(nclaim, (uint32_t)D.max_active)) > room) abort_code = E_HISTORY_OVERFLOW;
     else if (nclaim <= (uint32_t)D.max_active) {
       // nothing can be pruned: every token within the beam is kept
       for (uint32_t i = tid; i < n_q; i += NT) {
@@ -276,7 +276,11 @@ __device__ void general_frame(const DecDev &D, LaneShared<NT> &S, const float *l
       __syncthreads();
       const int n = (int)S.nvalid;
       uint32_t theta = KEY_NONE, h_theta = 0xFFFFFFFFu;       // keep key < theta, or == theta with handle <= h_theta
-      if (n > D.max_active) {
+      if (n > D.max_active && D.approximate) {
+        theta = block_histogram_cut<NT>(S, n, (uint32_t)D.max_active, S.kmin, S.kmax,
+                                        [&](int i, uint32_t &v) { v = dkey[i]; return true; });
+        cutoff_eff = key2f(theta);                            // (every key <= theta is kept)
+      } else if (n > D.max_active) {
         uint32_t n_less, n_eq;
         block_select<NT>(S, n, (uint32_t)D.max_active, S.kmin, S.kmax,
                          [&](int i, uint32_t &v) { v = dkey[i]; return true; }, theta, n_less, n_eq);
@@ -310,7 +314,7 @@ __device__ void general_frame(const DecDev &D, LaneShared<NT> &S, const float *l
   }
   __syncthreads();
   GEN_MARK(2);
-  const uint32_t n_out = (abort_code == 0) ? min(S.nout, (uint32_t)D.max_active) : 0u;
+  const uint32_t n_out = (abort_code == 0) ? (D.approximate ? S.nout : min(S.nout, (uint32_t)D.max_active)) : 0u;
 
   // ---- 5. lattice records and back-pointers ---------------------------------------------
   if (abort_code == 0) {

@@ -338,7 +338,7 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
   uint32_t eps_cnt = 0;
   if (abort_code == 0) {
     const uint32_t room = (uint32_t)min((long long)0x7FFFFFFF, D.hist_cap - out_base);
-    if (min(nclaim, (uint32_t)D.max_active) > room) abort_code = E_HISTORY_OVERFLOW;
+    if ((D.approximate ? nclaim : min(nclaim, (uint32_t)D.max_active)) > room) abort_code = E_HISTORY_OVERFLOW;
     else if (nclaim <= (uint32_t)D.max_active) {
       // nothing can be pruned: every token within the beam is kept
       for (uint32_t i = tid; i < n_q; i += NT) {
@@ -372,7 +372,11 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
       __syncthreads();
       const int n = (int)uni(C.nvalid);
       uint32_t theta = KEY_NONE, h_theta = 0xFFFFFFFFu;       // keep key < theta, or == theta with handle <= h_theta
-      if (n > D.max_active) {
+      if (n > D.max_active && D.approximate) {
+        theta = block_histogram_cut<NT>(S, n, (uint32_t)D.max_active, uni(C.kmin), uni(C.kmax),
+                                        [&](int i, uint32_t &v) { v = dkey[i]; return true; });
+        cutoff_eff = key2f(theta);                            // (every key <= theta is kept)
+      } else if (n > D.max_active) {
         uint32_t n_less, n_eq;
         block_select<NT>(S, n, (uint32_t)D.max_active, uni(C.kmin), uni(C.kmax),
                          [&](int i, uint32_t &v) { v = dkey[i]; return true; }, theta, n_less, n_eq);
@@ -408,7 +412,7 @@ __device__ bool light_frame(const DecDev &D, LaneShared<NT> &S, LaneCtx &ctx, co
   lds_barrier();
   PHASE_MARK(8);
   const uint32_t nout_all = uni(C.nout);
-  const uint32_t n_out = (abort_code == 0) ? min(nout_all, (uint32_t)D.max_active) : 0u;
+  const uint32_t n_out = (abort_code == 0) ? (D.approximate ? nout_all : min(nout_all, (uint32_t)D.max_active)) : 0u;
   const uint32_t n_valid = (abort_code == 0) ? max(uni(C.nvalid), nout_all) : 0u;
 
   // ---- 5. history records, back-pointers and lattice records ---------------------------------

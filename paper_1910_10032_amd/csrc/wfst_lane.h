@@ -337,4 +337,38 @@ __device__ void block_select(LaneShared<NT> &S, int n, uint32_t need, uint32_t l
   }
 }
 
+// The approximate form of the selection (the paper's histogram-based max-active, Section 4.1):
+// ONE histogram of NBINS equal-width bins over [lo, hi]; the cut is the upper edge of the bin in
+// which the running count reaches `need`, so up to that bin's population more than `need`
+// values lie at or below it.  Integer counting only: the same cut whatever the thread order.
+template <int NT, class F>
+__device__ uint32_t block_histogram_cut(LaneShared<NT> &S, int n, uint32_t need, uint32_t lo, uint32_t hi, F val) {
+  const int tid = threadIdx.x;
+  constexpr int PER = NBINS / NT;
+  int shift = 0;
+  while ((((unsigned long long)hi - lo) >> shift) >= (unsigned long long)NBINS) ++shift;
+  for (int b = tid; b < NBINS; b += NT) S.hist[b] = 0;
+  __syncthreads();
+  for (int i = tid; i < n; i += NT) {
+    uint32_t v;
+    if (val(i, v) && v >= lo && v <= hi) atomicAdd(&S.hist[(v - lo) >> shift], 1u);
+  }
+  __syncthreads();
+  uint32_t loc[PER], sum = 0;
+#pragma unroll
+  for (int q = 0; q < PER; ++q) { loc[q] = S.hist[tid * PER + q]; sum += loc[q]; }
+  int total;
+  uint32_t run = (uint32_t)block_excl_scan<NT>((int)sum, S.wave_tmp, total);
+#pragma unroll
+  for (int q = 0; q < PER; ++q) {
+    if (run < need && run + loc[q] >= need) S.sel_bin = tid * PER + q;
+    run += loc[q];
+  }
+  __syncthreads();
+  const uint32_t b = S.sel_bin;
+  __syncthreads();
+  const unsigned long long edge = (unsigned long long)lo + ((unsigned long long)(b + 1) << shift) - 1ull;
+  return edge < hi ? (uint32_t)edge : hi;
+}
+
 }  // namespace wfst
