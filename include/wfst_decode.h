@@ -125,6 +125,17 @@ typedef struct {
                                 checker's result wherever max-active binds; identical to the
                                 exact mode wherever it does not.  The default
                                 history_capacity is a quarter larger in this mode.            */
+  int32_t lane_workgroups;   /* 0 or 1: one workgroup per lane.  G > 1 (at most 64): a call
+                                without snapshots whose lanes are so few that 2 * lanes <= the
+                                device's compute units gives every lane min(G, units / lanes)
+                                workgroups of 1024 threads that work through each frame
+                                together (Section 3.1: small batches leave the device idle and
+                                are bound by latency; Section 3.3: the persistent kernel).  For
+                                single or few heavy streams; every frame then takes the general
+                                form and pays a device-wide barrier per stage, so light streams
+                                are slower this way.  Results do not depend on it.  If a
+                                barrier is ever given up (a workgroup of the lane not resident
+                                for seconds) the channel stops with WFST_E_DEVICE.            */
 } wfst_config_t;
 
 typedef struct { int32_t frame; uint32_t arc; float extra_cost; } wfst_lat_arc_t;

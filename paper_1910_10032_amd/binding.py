@@ -43,7 +43,7 @@ class wfst_config_t(C.Structure):
                 ("num_channels", C.c_int32), ("max_lanes", C.c_int32), ("max_frames", C.c_int32),
                 ("token_capacity", C.c_int32), ("aux_capacity", C.c_int32), ("history_capacity", C.c_int64),
                 ("lattice_capacity", C.c_int64), ("lattice_on", C.c_int32), ("snapshot_blocks", C.c_int32),
-                ("snapshot_block_capacity", C.c_int64), ("lane_threads", C.c_int32), ("frame_form", C.c_int32), ("approximate", C.c_int32)]
+                ("snapshot_block_capacity", C.c_int64), ("lane_threads", C.c_int32), ("frame_form", C.c_int32), ("approximate", C.c_int32), ("lane_workgroups", C.c_int32)]
 
 
 class wfst_stats_t(C.Structure):
@@ -161,11 +161,11 @@ class WfstDecoder:
                  max_lanes: int, max_frames: int, token_capacity: int = 0, aux_capacity: int = 0,
                  history_capacity: int = 0, lattice_capacity: int = 0, lattice_on: bool = True,
                  snapshot_blocks: int = 0, snapshot_block_capacity: int = 0, lane_threads: int = 0,
-                 frame_form: int = 0, approximate: bool = False):
+                 frame_form: int = 0, approximate: bool = False, lane_workgroups: int = 0):
         self.graph = graph
         self.cfg = wfst_config_t(beam, lattice_beam, max_active, num_channels, max_lanes, max_frames, token_capacity,
                                  aux_capacity, history_capacity, lattice_capacity, int(lattice_on), snapshot_blocks,
-                                 snapshot_block_capacity, lane_threads, frame_form, int(approximate))
+                                 snapshot_block_capacity, lane_threads, frame_form, int(approximate), lane_workgroups)
         self.h = C.c_void_p()
         _check(lib().wfst_decode_create(graph.h, C.byref(self.cfg), C.byref(self.h)), "wfst_decode_create")
 

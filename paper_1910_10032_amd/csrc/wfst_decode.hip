@@ -45,6 +45,7 @@ struct wfst_decoder {
   std::vector<uint32_t> stamp;          // duplicate detection within a call
   uint32_t stamp_now = 0;
   LaneParam *d_params = nullptr;        // [max_lanes]
+  WideLane *d_wide = nullptr;           // [max_lanes] lanes shared by several workgroups (lane_workgroups > 1)
   LaneParam *h_params[PARAM_RING] = {};
   hipEvent_t param_ev[PARAM_RING] = {};
   int ring_pos = 0;
@@ -131,8 +132,10 @@ int check_channels(wfst_decoder *d, const int32_t *channels, int32_t n, bool nee
   return 0;
 }
 
-// Stage lane parameters through a pinned ring and launch the lane kernel.
-int launch_lanes(wfst_decoder *d, const std::vector<LaneParam> &lp, int is_init, hipStream_t stream) {
+// Stage lane parameters through a pinned ring and launch the lane kernel.  wide: several
+// workgroups per lane (only for calls without snapshots whose lanes x workgroups fit the device
+// at one workgroup per compute unit, so that all of them are resident and can wait for each other).
+int launch_lanes(wfst_decoder *d, const std::vector<LaneParam> &lp, int is_init, hipStream_t stream, bool wide = false) {
   const int n = (int)lp.size();
   if (n == 0) return 0;
   const int slot = d->ring_pos;
@@ -149,6 +152,14 @@ int launch_lanes(wfst_decoder *d, const std::vector<LaneParam> &lp, int is_init,
   // A lane is one workgroup.  With at most one lane per compute unit a lane can have the whole
   // unit: 1024 threads; with more lanes two 512-thread workgroups share a unit.  The results
   // do not depend on the choice.
+  if (wide) {
+    const int G = std::min(d->cfg.lane_workgroups, d->num_cus / n);
+    hipLaunchKernelGGL(k_zero_wide, dim3((n + 63) / 64), dim3(64), 0, stream, d->d_wide, n);
+    hipLaunchKernelGGL(k_advance_wide<1024>, dim3(n * G), dim3(1024), 0, stream, d->dev, (const LaneParam *)d->d_params, d->d_wide, G);
+    HIP_TRY(hipGetLastError());
+    if (e0) { HIP_TRY(hipEventRecord(e1, stream)); d->prof_events.push_back({e0, e1}); }
+    return 0;
+  }
   int threads = d->cfg.lane_threads;
   if (threads == 0) threads = n <= d->num_cus ? 1024 : NT;
   if (threads == 1024)
@@ -327,6 +338,7 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
   if (c.lane_threads != 0 && c.lane_threads != 256 && c.lane_threads != 512 && c.lane_threads != 1024) return WFST_E_INVALID_ARG;
   if (c.frame_form != 0 && c.frame_form != 1) return WFST_E_INVALID_ARG;
   if (c.approximate != 0 && c.approximate != 1) return WFST_E_INVALID_ARG;
+  if (c.lane_workgroups < 0 || c.lane_workgroups > 64) return WFST_E_INVALID_ARG;
   if (!c.lattice_on) c.snapshot_blocks = 0;
   if (c.snapshot_blocks > 0 && c.snapshot_block_capacity == 0)
     c.snapshot_block_capacity = std::min<int64_t>(c.lattice_capacity, 4096ll * c.max_lanes);
@@ -372,6 +384,7 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
   if (!rc) rc = dev_alloc(d, &D.dkey, nl * (size_t)D.tokcap);
   if (!rc) rc = dev_alloc(d, &D.dslot, nl * (size_t)D.tokcap);
   if (!rc) rc = dev_alloc(d, &d->d_params, nl);
+  if (!rc && c.lane_workgroups > 1) rc = dev_alloc(d, &d->d_wide, nl);
   d->per_lane_bytes = (d->total_bytes - before_lanes) / (int64_t)nl;
   if (!rc) rc = dev_alloc(d, &d->d_chans, std::max(nc, nl));
   if (!rc) rc = dev_alloc(d, &d->d_pathout, std::max(nc, nl));
@@ -509,7 +522,8 @@ static int advance_impl(wfst_decoder_t *d, const int32_t *channels, int32_t n_la
     HIP_TRY(hipGetLastError());
     for (int32_t j = 0; j < n_snaps; ++j) d->blk_ids[(size_t)((id0 + j) % d->dev.n_blk)] = id0 + j;
   }
-  rc = launch_lanes(d, lp, 0, (hipStream_t)stream);
+  const bool wide = d->cfg.lane_workgroups > 1 && n_snaps == 0 && 2 * n_lanes <= d->num_cus;
+  rc = launch_lanes(d, lp, 0, (hipStream_t)stream, wide);
   if (rc) return rc;
   HIP_TRY(hipEventRecord(d->last_advance, (hipStream_t)stream));
   d->have_last_advance = true;

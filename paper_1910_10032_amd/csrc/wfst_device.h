@@ -154,6 +154,6 @@ struct DecDev {
 
 // error codes mirrored from the public header (device code cannot include it cleanly)
 constexpr int E_TOKEN_OVERFLOW = -6, E_LATTICE_OVERFLOW = -7, E_DEAD_CHANNEL = -8, E_NAN_INPUT = -9,
-              E_BROKEN_TRACE = -10, E_HISTORY_OVERFLOW = -12, E_CAPACITY = -5, E_NOT_INIT = -4;
+              E_BROKEN_TRACE = -10, E_DEVICE = -11, E_HISTORY_OVERFLOW = -12, E_CAPACITY = -5, E_NOT_INIT = -4;
 
 }  // namespace wfst

@@ -55,7 +55,7 @@ __global__ void __launch_bounds__(NT, NT >= 512 ? 4 : 2) k_advance(DecDev D, con
     reset_ctr(S.fc[0]); reset_ctr(S.fc[1]);
     if (is_init) foff[0] = 0;
 #ifdef WFST_PHASE_TIMING
-    for (int k = 0; k < 16; ++k) S.ph[k] = 0;
+    for (int k = 0; k < 16; ++k) { S.ph[k] = 0; S.gph[k] = 0; }
     S.dbg_tok = 0; S.dbg_iters = 0; S.dbg_arcs = 0;
 #endif
   }
@@ -160,7 +160,8 @@ __global__ void __launch_bounds__(NT, NT >= 512 ? 4 : 2) k_advance(DecDev D, con
       S.lat_total = ctx.lat_total; S.lat_pos = ctx.lat_pos; S.arcs_expanded = ctx.arcs_expanded;
     }
     __syncthreads();                                  // (also: the light frames' history stores have arrived)
-    general_frame<NT>(D, S, ll, is_init != 0, D.slots + (size_t)blockIdx.x * D.H, D.queue + (size_t)blockIdx.x * (size_t)D.qcap,
+    WideCtx none{0, 1, nullptr, 0ull};
+    general_frame<NT, false>(D, S, none, ll, is_init != 0, D.slots + (size_t)blockIdx.x * D.H, D.queue + (size_t)blockIdx.x * (size_t)D.qcap,
                       D.aux + (size_t)blockIdx.x * (size_t)D.auxcap, D.dkey + (size_t)blockIdx.x * (size_t)D.tokcap,
                       D.dslot + (size_t)blockIdx.x * (size_t)D.tokcap, foff, D.hist + (size_t)lp.chan * (size_t)D.hist_cap, lat);
     ctx.status = uni(S.status); ctx.nf = uni(S.nf); ctx.n_in = uni(S.n_in); ctx.max_pre = uni(S.max_pre); ctx.max_post = uni(S.max_post);
@@ -210,7 +211,7 @@ __global__ void __launch_bounds__(NT, NT >= 512 ? 4 : 2) k_advance(DecDev D, con
     cs->lat_head = ctx.lat_head;
 #ifdef WFST_PHASE_TIMING
     if (D.dbg) {
-      for (int k = 0; k < 16; ++k) atomicAdd(D.dbg + k, S.ph[k]);
+      for (int k = 0; k < 16; ++k) { atomicAdd(D.dbg + k, S.ph[k]); atomicAdd(D.dbg + 16 + 10240 + k, S.gph[k]); }
       unsigned long long tot = 0;
       for (int k = 0; k < 16; ++k) if (k != 5 && k != 6 && k != 7 && k != 13) tot += S.ph[k];
       D.dbg[16 + blockIdx.x] = tot;                     // this lane's time for the call
@@ -221,6 +222,56 @@ __global__ void __launch_bounds__(NT, NT >= 512 ? 4 : 2) k_advance(DecDev D, con
     }
 #endif
   }
+}
+
+// Several workgroups per lane (blockIdx.x = lane * G + g): every frame in the general form, the
+// lane's G workgroups working through it together (see WideCtx).  Every workgroup keeps its own
+// replica of the lane's state; workgroup 0 of the lane writes it back.  For calls with so few
+// lanes that the device would otherwise stand idle; no snapshots.
+template <int NT>
+__global__ void __launch_bounds__(NT, 4) k_advance_wide(DecDev D, const LaneParam *__restrict__ lanes, WideLane *wide, int G) {
+  __shared__ LaneShared<NT> S;
+  const int tid = threadIdx.x;
+  const int lane = blockIdx.x / G, g = blockIdx.x % G;
+  const LaneParam lp = lanes[lane];
+  ChanState *cs = D.chan + lp.chan;
+  long long *foff = D.frame_off + (size_t)lp.chan * (size_t)(D.max_frames + 2);
+  if (tid == 0) {
+    S.status = cs->status; S.nf = cs->num_frames; S.hist_used = cs->hist_used;
+    S.lat_total = cs->lat_total;
+    S.lat_room = D.lat_cap - (cs->lat_total - cs->lat_head);
+    S.lat_pos = cs->lat_total % D.lat_cap;
+    S.arcs_expanded = cs->arcs_expanded; S.max_pre = cs->max_pre; S.max_post = cs->max_post; S.iters_max = cs->closure_iters_max;
+    S.in_off = 0; S.n_in = 0;
+    if (S.nf >= 1 && S.nf <= D.max_frames + 1) { S.in_off = foff[S.nf - 1]; S.n_in = (int)(foff[S.nf] - foff[S.nf - 1]); }
+#ifdef WFST_PHASE_TIMING
+    for (int k = 0; k < 16; ++k) { S.ph[k] = 0; S.gph[k] = 0; }
+    S.dbg_tok = 0; S.dbg_iters = 0; S.dbg_arcs = 0;
+#endif
+  }
+  __syncthreads();
+  WideCtx W{g, G, wide + lane, 0ull};
+  for (int f = 0; f < lp.n_frames && S.status == 0; ++f) {
+    general_frame<NT, true>(D, S, W, lp.ll + (size_t)f * (size_t)lp.stride, false, D.slots + (size_t)lane * D.H,
+                            D.queue + (size_t)lane * (size_t)D.qcap, D.aux + (size_t)lane * (size_t)D.auxcap,
+                            D.dkey + (size_t)lane * (size_t)D.tokcap, D.dslot + (size_t)lane * (size_t)D.tokcap, foff,
+                            D.hist + (size_t)lp.chan * (size_t)D.hist_cap, D.lat + (size_t)lp.chan * (size_t)D.lat_cap);
+  }
+  __syncthreads();
+  if (g == 0 && tid == 0) {
+    // (a barrier that was given up leaves the lane's state incomplete: the channel stops with a device error)
+    cs->status = ld32(&wide[lane].broken) && S.status == 0 ? E_DEVICE : S.status;
+    cs->num_frames = S.nf; cs->hist_used = S.hist_used;
+    cs->lat_total = S.lat_total; cs->arcs_expanded = S.arcs_expanded; cs->max_pre = S.max_pre;
+    cs->max_post = S.max_post; cs->closure_iters_max = S.iters_max;
+#ifdef WFST_PHASE_TIMING
+    if (D.dbg) { for (int k = 0; k < 16; ++k) atomicAdd(D.dbg + 16 + 10240 + k, S.gph[k]); atomicAdd(D.dbg + 6, (unsigned long long)lp.n_frames); atomicAdd(D.dbg + 5, (unsigned long long)lp.n_frames); }
+#endif
+  }
+}
+__global__ void k_zero_wide(WideLane *wide, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) { wide[i].arrived = 0ull; wide[i].broken = 0u; }
 }
 
 __global__ void k_fill_slots(Slot *slots, size_t n) {

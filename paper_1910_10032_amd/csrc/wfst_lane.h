@@ -4,6 +4,8 @@
 #include "wfst_device.h"
 
 namespace wfst {
+
+constexpr int NBINS = 1024;
 // ---- wavefront primitives (all 64 lanes must be active) ------------------------------------
 template <int CTRL> __device__ __forceinline__ int dpp_mov(int old, int v) {
   return __builtin_amdgcn_update_dpp(old, v, CTRL, 0xF, 0xF, false);
@@ -134,7 +136,6 @@ __device__ __forceinline__ float uni(float v) { return __uint_as_float(uni(__flo
 
 
 
-constexpr int NBINS = 1024;
 
 __device__ __forceinline__ uint32_t okey(float x) {
   uint32_t b = __float_as_uint(x);
@@ -215,6 +216,24 @@ constexpr uint32_t AUX_EPS = 0x80000000u;  // Aux::slot flag: the record is an e
 constexpr uint32_t A_FRESH = 0x80000000u;  // epsilon out-degree not counted yet
 constexpr uint32_t A_KEPT_MAX = 0x20000000u;  // aux < A_KEPT_MAX: index of the kept token
 
+// Counters of a general frame: in LDS when one workgroup owns the lane, in global memory when
+// several do (then read with loads that bypass the vector cache).
+struct GenCtr {
+  // queue entries (low word) and states claimed (high word) of the frame: one 64-bit counter,
+  // so that a claim takes one atomic for both
+  unsigned long long claim_ctr;
+  unsigned long long emit_arcs, eps_arcs;
+  uint32_t auxn, best, flags, nvalid, nout, latn, kmin, kmax;
+};
+// A lane shared by several workgroups: its counters, the selection's histogram and the count
+// of workgroups that have arrived at the lane's barriers so far.
+struct WideLane {
+  GenCtr c;
+  uint32_t hist[3][NBINS];     // the selection's passes rotate through three histograms (see wide_select)
+  unsigned long long arrived;
+  uint32_t broken, pad;
+};
+
 // LDS of a lane's workgroup.
 template <int NT>
 struct LaneShared {
@@ -227,18 +246,15 @@ struct LaneShared {
   };
   // -- general frame: its counters, and the lane's state while such a frame runs (between light
   //    frames the state lives in registers, see LaneCtx)
-  // queue entries (low word) and states claimed (high word) of the frame: one 64-bit counter,
-  // so that a claim takes one atomic for both
-  union { unsigned long long claim_ctr; struct { uint32_t qtail, nclaim; }; };
-  uint32_t auxn, best, flags, nvalid, nout, latn, kmin, kmax;
+  GenCtr gen;                  // the general frame's counters (one workgroup per lane)
   uint32_t sel_bin, sel_below, sel_cnt;
-  unsigned long long emit_arcs, eps_arcs;
+  uint32_t wide_ok;            // outcome of the last lane barrier (lanes shared by several workgroups)
   int status, nf, max_pre, max_post, iters_max, n_in;
   long long in_off, hist_used, lat_room, lat_total, arcs_expanded;
   long long lat_pos;           // ring position of record number lat_total
   long long blk_pos;           // seal scratch
 #ifdef WFST_PHASE_TIMING
-  unsigned long long ph[16], dbg_tok, dbg_iters, dbg_arcs;
+  unsigned long long ph[16], gph[16], gtlast, dbg_tok, dbg_iters, dbg_arcs;
 #endif
   // -- light frame
   FrameCtr fc[2];
@@ -256,7 +272,11 @@ struct LaneShared {
 #else
 #define PHASE_MARK(k) do { } while (0)
 #endif
-#define GEN_MARK(k) do { } while (0)        // the general frame is timed as a whole
+#ifdef WFST_PHASE_TIMING
+#define GEN_MARK(k) do { if (threadIdx.x == 0) { unsigned long long t_ = wall_clock64(); S.gph[k] += t_ - S.gtlast; S.gtlast = t_; } } while (0)
+#else
+#define GEN_MARK(k) do { } while (0)
+#endif
 
 // Workgroup barrier for stages that communicate through LDS only: it orders LDS accesses but
 // does not wait for global loads or stores in flight, so the score-row touch and the stores of

@@ -694,3 +694,40 @@ def test_two_decoders_share_a_graph_on_two_streams(torch_cuda, B):
     for k, d in enumerate(decs):
         for i in range(3):
             compare_channel(d, i, ods[3 * k + i], label=f"decoder {k} ch {i}", lattice=not (k == 1 and i == 1))
+
+
+@pytest.mark.parametrize("G", [2, 5, 16])
+def test_several_workgroups_per_lane(torch_cuda, B, G):
+    """lane_workgroups > 1: the lane's workgroups work through every frame together (counters
+    and the selection's histogram in global memory, lane barriers between the stages).  Same
+    bits as one workgroup per lane: a heavy single stream (config 1: thousands of tokens,
+    max-active binding), several small streams side by side, exact ties, and the approximate cut."""
+    c = synth.configs()[1]
+    g = synth.make_graph(c.graph)
+    rows = [c.loglikes(1, 0, 30)]
+    dec, ods, _ = run_pair(torch_cuda, B, g, rows, c.beam, c.lattice_beam, c.max_active, token_capacity=1 << 16,
+                           lattice_capacity=1 << 21, lane_workgroups=G)
+    assert ods[0].max_tokens_pre_prune > c.max_active
+    compare_channel(dec, 0, ods[0], label=f"cfg1 G={G}")
+    # the approximate cut gives the same bytes with one and with several workgroups
+    one = run_pair(torch_cuda, B, g, rows, c.beam, c.lattice_beam, c.max_active, token_capacity=1 << 16,
+                   lattice_capacity=1 << 21, approximate=True)[0]
+    many = run_pair(torch_cuda, B, g, rows, c.beam, c.lattice_beam, c.max_active, token_capacity=1 << 16,
+                    lattice_capacity=1 << 21, approximate=True, lane_workgroups=G)[0]
+    for f in (5, 17, 30):
+        a, b = one.tokens(0, f), many.tokens(0, f)
+        assert np.array_equal(np.sort(a, order="state"), np.sort(b, order="state"))
+    # several lanes, chunked calls, ragged lengths
+    c0 = synth.configs()[0]
+    g0 = synth.make_graph(c0.graph)
+    rows0 = [c0.loglikes(s, 0, n) for s, n in enumerate((60, 35, 48))]
+    dec, ods, _ = run_pair(torch_cuda, B, g0, rows0, c0.beam, c0.lattice_beam, c0.max_active, chunks=[20, 20, 20],
+                           lattice_capacity=1 << 19, lane_workgroups=G)
+    for ch, od in enumerate(ods):
+        compare_channel(dec, ch, od, label=f"cfg0 G={G} ch{ch}")
+    # exact ties at the max-active cut
+    rng = np.random.default_rng(5)
+    gt = random_graph(rng, num_states=400, n_emit_per_state=(3, 6), eps_prob=0.004, num_pdfs=4, wmax=2, integer=True)
+    rt = [-rng.integers(0, 2, size=(15, 4)).astype(F32)]
+    dec, ods, _ = run_pair(torch_cuda, B, gt, rt, beam=6.0, lbeam=2.0, alpha=37, token_capacity=2048, lane_workgroups=G)
+    compare_channel(dec, 0, ods[0], label=f"ties G={G}")
