@@ -235,9 +235,12 @@ def test_max_active_binds_on_the_8m_state_graph(lane_threads, max_active, n_fram
     assert len(binding) >= 12 and all(s["max_tokens"] == max_active for s in binding)
 
 
-def test_config1_whole_stream_with_max_active_binding():
+@pytest.mark.parametrize("lane_workgroups", [0, 16])
+def test_config1_whole_stream_with_max_active_binding(lane_workgroups):
     """Config 1: one stream of 1000 frames on the 200k-state graph, ~26k tokens before and 7000
     after pruning in nearly every frame, so the exact max-active selection runs a thousand
-    times at different places of the cost range; every frame is compared."""
+    times at different places of the cost range; every frame is compared.  Once with one
+    workgroup on the lane, once with sixteen working through every frame together."""
     cfg = synth.configs()[1]
-    decode_and_compare(cfg, sample=[0], token_capacity=1 << 16, history_capacity=8_000_000, lattice_capacity=8_000_000)
+    decode_and_compare(cfg, sample=[0], token_capacity=1 << 16, history_capacity=8_000_000, lattice_capacity=8_000_000,
+                       lane_workgroups=lane_workgroups)
