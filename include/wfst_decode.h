@@ -135,7 +135,10 @@ typedef struct {
                                 form and pays a device-wide barrier per stage, so light streams
                                 are slower this way.  Results do not depend on it.  If a
                                 barrier is ever given up (a workgroup of the lane not resident
-                                for seconds) the channel stops with WFST_E_DEVICE.            */
+                                for seconds) the channel stops with WFST_E_DEVICE.  (Testing
+                                aid: the environment variable WFST_DECODE_WIDE_SPIN_LIMIT,
+                                read when a decoder is created, lowers the number of polls
+                                after which a barrier is given up.)                           */
 } wfst_config_t;
 
 typedef struct { int32_t frame; uint32_t arc; float extra_cost; } wfst_lat_arc_t;

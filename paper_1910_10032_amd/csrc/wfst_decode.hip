@@ -6,6 +6,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <deque>
@@ -364,6 +365,11 @@ int wfst_decode_create(const wfst_graph_t *graph, const wfst_config_t *config, w
   D.lattice_on = c.lattice_on ? 1 : 0; D.beam = c.beam; D.lattice_beam = c.lattice_beam;
   D.force_general = c.frame_form == 1 ? 1 : 0;
   D.approximate = c.approximate;
+  D.wide_spin_limit = WIDE_SPIN_LIMIT;
+  if (const char *e = std::getenv("WFST_DECODE_WIDE_SPIN_LIMIT")) {   // a testing aid: give lane barriers up early
+    const long v = std::strtol(e, nullptr, 10);
+    if (v >= 1 && v <= (long)WIDE_SPIN_LIMIT) D.wide_spin_limit = (uint32_t)v;
+  }
   D.hist_cap = c.history_capacity; D.lat_cap = c.lattice_on ? c.lattice_capacity : 1;
   const size_t nc = (size_t)c.num_channels, nl = (size_t)c.max_lanes;
   int rc = 0;

@@ -149,6 +149,8 @@ struct DecDev {
   float beam, lattice_beam;
   int32_t force_general;         // 1: every frame takes the general form
   int32_t approximate;           // 1: max-active by a single histogram cut (not exact)
+  uint32_t wide_spin_limit;      // polls before a lane barrier is given up (lanes shared by several workgroups)
+  int32_t pad3;
   unsigned long long *dbg;   // phase timers of instrumented builds, else null
 };
 

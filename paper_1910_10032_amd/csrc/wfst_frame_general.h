@@ -14,8 +14,9 @@ struct WideCtx {
   int g, G;                    // this workgroup's number among the lane's, and how many there are
   WideLane *wl;
   unsigned long long epoch;    // arrivals expected at the next barrier (thread 0 keeps count)
+  unsigned spin_limit;
 };
-constexpr unsigned WIDE_SPIN_LIMIT = 1u << 22;      // polls before a barrier is given up (seconds)
+constexpr unsigned WIDE_SPIN_LIMIT = 1u << 22;      // default number of polls before a barrier is given up (seconds)
 
 // Returns false (to every thread of the workgroup) if a barrier of the lane was given up: the
 // workgroup must then stop working on the lane (what it would read may be incomplete).
@@ -30,7 +31,7 @@ __device__ __forceinline__ bool lane_sync(WideCtx &W, LaneShared<NT> &S) {
       atomicAdd(&W.wl->arrived, 1ull);
       unsigned spins = 0;
       while (ld64(&W.wl->arrived) < W.epoch) {
-        if (++spins > WIDE_SPIN_LIMIT || ld32(&W.wl->broken)) { atomicExch(&W.wl->broken, 1u); ok = false; break; }
+        if (++spins > W.spin_limit || ld32(&W.wl->broken)) { atomicExch(&W.wl->broken, 1u); ok = false; break; }
         __builtin_amdgcn_s_sleep(4);
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");

@@ -160,7 +160,7 @@ __global__ void __launch_bounds__(NT, NT >= 512 ? 4 : 2) k_advance(DecDev D, con
       S.lat_total = ctx.lat_total; S.lat_pos = ctx.lat_pos; S.arcs_expanded = ctx.arcs_expanded;
     }
     __syncthreads();                                  // (also: the light frames' history stores have arrived)
-    WideCtx none{0, 1, nullptr, 0ull};
+    WideCtx none{0, 1, nullptr, 0ull, 0u};
     general_frame<NT, false>(D, S, none, ll, is_init != 0, D.slots + (size_t)blockIdx.x * D.H, D.queue + (size_t)blockIdx.x * (size_t)D.qcap,
                       D.aux + (size_t)blockIdx.x * (size_t)D.auxcap, D.dkey + (size_t)blockIdx.x * (size_t)D.tokcap,
                       D.dslot + (size_t)blockIdx.x * (size_t)D.tokcap, foff, D.hist + (size_t)lp.chan * (size_t)D.hist_cap, lat);
@@ -250,7 +250,7 @@ __global__ void __launch_bounds__(NT, 4) k_advance_wide(DecDev D, const LanePara
 #endif
   }
   __syncthreads();
-  WideCtx W{g, G, wide + lane, 0ull};
+  WideCtx W{g, G, wide + lane, 0ull, D.wide_spin_limit};
   for (int f = 0; f < lp.n_frames && S.status == 0; ++f) {
     general_frame<NT, true>(D, S, W, lp.ll + (size_t)f * (size_t)lp.stride, false, D.slots + (size_t)lane * D.H,
                             D.queue + (size_t)lane * (size_t)D.qcap, D.aux + (size_t)lane * (size_t)D.auxcap,

@@ -731,3 +731,26 @@ def test_several_workgroups_per_lane(torch_cuda, B, G):
     rt = [-rng.integers(0, 2, size=(15, 4)).astype(F32)]
     dec, ods, _ = run_pair(torch_cuda, B, gt, rt, beam=6.0, lbeam=2.0, alpha=37, token_capacity=2048, lane_workgroups=G)
     compare_channel(dec, 0, ods[0], label=f"ties G={G}")
+
+
+def test_a_lane_barrier_that_is_given_up_stops_the_channel_and_the_kernel_still_ends(torch_cuda, B, monkeypatch):
+    """Several workgroups per lane wait for each other a bounded number of polls.  With the bound
+    forced down to one poll (from the host: every kernel still exits normally) barriers are given
+    up: the call returns, the channel either finished correctly or stopped with WFST_E_DEVICE, and
+    a decoder created without the bound works as usual afterwards."""
+    c = synth.configs()[0]
+    g = synth.make_graph(c.graph)
+    rows = [c.loglikes(0, 0, 40)]
+    monkeypatch.setenv("WFST_DECODE_WIDE_SPIN_LIMIT", "1")
+    gg = B.WfstGraph(g)
+    dec = B.WfstDecoder(gg, c.beam, c.lattice_beam, c.max_active, num_channels=1, max_lanes=1, max_frames=40, lane_workgroups=16)
+    dec.init_channels([0])
+    dec.advance([0], [torch_cuda.from_numpy(rows[0]).cuda()])
+    torch_cuda.cuda.synchronize()
+    st = dec.stats(0)
+    assert st["status"] in (0, B.WFST_E_DEVICE)
+    if st["status"] == 0:
+        assert st["frames"] == 41
+    monkeypatch.delenv("WFST_DECODE_WIDE_SPIN_LIMIT")
+    dec2, ods, _ = run_pair(torch_cuda, B, g, rows, c.beam, c.lattice_beam, c.max_active, lane_workgroups=16, lattice_capacity=1 << 19)
+    compare_channel(dec2, 0, ods[0], label="after a given-up barrier")
