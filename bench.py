@@ -40,7 +40,8 @@ sys.path.insert(0, ROOT)
 
 FRAME_SHIFT_S = 0.010
 HBM_PEAK_GBS = 8000.0
-# Algorithmic HBM bytes (what the method itself must move):
+# Algorithmic HBM bytes - what the method itself must move per unit of work, whatever the
+# implementation fetches on top (cache-line granularity, re-reads):
 BYTES_PER_ARC = 16.0      # 12-byte arc record + 4-byte score
 BYTES_PER_TOKEN = 44.0    # 12-byte state record + 16-byte token read when expanded + 16-byte token written
 BYTES_PER_LAT = 12.0      # one lattice record

@@ -394,7 +394,9 @@ int wfst_decode_profile(wfst_decoder_t *decoder, int64_t *launches, double *tota
  *   wfst_mux_submit   loglikes: DEVICE rows [n_frames][stride] (n_frames >= 1), valid until the
  *                     step that consumes them has completed on its stream
  *   wfst_mux_step     issues one advance call on `stream` (NULL: default stream) for the waiting
- *                     channels; *n_lanes = how many it bound (0: nothing was waiting, no call)
+ *                     channels; *n_lanes = how many it bound (0: nothing was waiting, no call).
+ *                     If the advance call fails (a channel beyond max_frames, say) its error is
+ *                     returned and the chunks bound in this step are dropped
  *   wfst_mux_pending  chunks submitted and not yet bound to a lane
  *   wfst_mux_stats    batches issued and lanes bound so far
  * Not thread-safe (one feeding thread per multiplexer). */

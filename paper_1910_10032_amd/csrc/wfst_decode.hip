@@ -1012,6 +1012,8 @@ int wfst_mux_step(wfst_mux_t *m, void *stream, int32_t *n_lanes) {
   }
   *n_lanes = (int32_t)m->lane_chan.size();
   if (*n_lanes == 0) return 0;
+  // (if the advance call refuses the batch - a channel beyond max_frames, say - the chunks bound
+  // here are dropped with it and the error is the caller's to handle)
   m->pending -= *n_lanes;
   ++m->batches; m->lanes_bound += *n_lanes;
   return wfst_decode_advance(d, m->lane_chan.data(), *n_lanes, m->lane_ll.data(), m->lane_stride.data(), m->lane_frames.data(), stream);
