@@ -754,3 +754,51 @@ def test_a_lane_barrier_that_is_given_up_stops_the_channel_and_the_kernel_still_
     monkeypatch.delenv("WFST_DECODE_WIDE_SPIN_LIMIT")
     dec2, ods, _ = run_pair(torch_cuda, B, g, rows, c.beam, c.lattice_beam, c.max_active, lane_workgroups=16, lattice_capacity=1 << 19)
     compare_channel(dec2, 0, ods[0], label="after a given-up barrier")
+
+
+def test_final_lattice_batch_capacity_and_dead_channels(torch_cuda, B):
+    """The batched final lattice: a buffer that is too small reports the needed size (offsets,
+    info and status still filled in, nothing written), a channel without a surviving token
+    reports its own status and contributes nothing, and the packed result equals the
+    single-channel calls."""
+    c = synth.configs()[0]
+    g = synth.make_graph(c.graph)
+    rows = [c.loglikes(s, 0, 40) for s in range(3)]
+    rows[1] = rows[1].copy(); rows[1][20, :] = -np.inf           # channel 1 dies at frame 21
+    dec, ods, _ = run_pair(torch_cuda, B, g, rows, c.beam, c.lattice_beam, c.max_active, lattice_capacity=1 << 19)
+    rec, offs, infos, st = dec.final_lattice_batch([0, 1, 2], True)
+    assert st.tolist() == [0, B.WFST_E_DEAD_CHANNEL, 0] and offs[2] == offs[1]
+    for k, ch in enumerate((0, 2)):
+        one, info = dec.final_lattice(ch, True)
+        got = rec[offs[ch]:offs[ch + 1]]
+        assert np.array_equal(np.sort(got, order=["frame", "arc"]), np.sort(one, order=["frame", "arc"])) and infos[ch] == info
+    import ctypes as C
+    need = int(offs[3])
+    out = np.zeros(max(need - 1, 1), B.LAT_DTYPE)
+    o2, s2 = np.zeros(4, np.int64), np.zeros(3, np.int32)
+    i2 = (B.wfst_lattice_info_t * 3)()
+    chans = np.array([0, 1, 2], np.int32)
+    rc = B.lib().wfst_decode_final_lattice_batch(dec.h, chans.ctypes.data, 3, 1, out.ctypes.data, need - 1, o2.ctypes.data, 0,
+                                                 C.cast(i2, C.c_void_p), s2.ctypes.data)
+    assert rc == B.WFST_E_CAPACITY and o2[3] == need and s2.tolist() == st.tolist() and not out["frame"].any()
+
+
+def test_argument_errors_of_the_newer_options(torch_cuda, B):
+    rng = np.random.default_rng(6)
+    g = random_graph(rng, num_states=10, n_emit_per_state=(1, 2), eps_prob=0.1, num_pdfs=3)
+    gg = B.WfstGraph(g)
+    for kw in (dict(lane_workgroups=65), dict(lane_workgroups=-1), dict(approximate=2), dict(frame_form=2)):
+        with pytest.raises(B.WfstError) as e:
+            B.WfstDecoder(gg, 5.0, 2.0, 10, num_channels=3, max_lanes=2, max_frames=4, **kw)
+        assert e.value.code == B.WFST_E_INVALID_ARG
+    dec = B.WfstDecoder(gg, 5.0, 2.0, 10, num_channels=3, max_lanes=2, max_frames=4)
+    dec.init_channels([0])
+    mux = B.WfstMux(dec)
+    t = torch_cuda.zeros((6, 3), dtype=torch_cuda.float32, device="cuda")
+    with pytest.raises(B.WfstError) as e:
+        mux.submit(1, t.data_ptr(), 3, 2)                   # channel 1 was never initialised
+    assert e.value.code == B.WFST_E_NOT_INIT
+    mux.submit(0, t.data_ptr(), 3, 6)                       # more frames than max_frames: the step reports it
+    with pytest.raises(B.WfstError) as e:
+        mux.step()
+    assert e.value.code == B.WFST_E_HISTORY_OVERFLOW and mux.pending() == 0
